@@ -1,0 +1,221 @@
+/*
+ * eagletv - teacher verification step of tree speculative decoding on AMD MI355X (gfx950).
+ *
+ * C ABI of the HIP library (libeagletv.so).  The five operations follow the
+ * problem statement of "EAGLE-Pangu" (arXiv 2603.08088): Section 2.4 / 3.3 (tree
+ * attention mask), Section 3.3 (tree-masked teacher attention over the committed
+ * prefix cache plus the speculative tokens), Section 3.2 (sentinel-free gathers
+ * through a valid dummy index), Section 2.3 / 5.1 (greedy posterior acceptance)
+ * and Section 3.1 (commit of the accepted path into the prefix cache).
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer unless its name starts with h_ (the
+ *    descriptor structs are host memory).  The caller owns every buffer,
+ *    including workspaces; the library never allocates, frees or keeps a pointer.
+ *  - Every launch call is asynchronous on `stream` (a hipStream_t passed as
+ *    void*; NULL = the default stream) and never synchronises the device.
+ *  - Return value: ETV_OK or a negative ETV_ERR_* for errors detectable on the
+ *    host (bad shapes, unsupported dtype, workspace too small, launch failure).
+ *    Data-dependent conditions (malformed tree, cache capacity) are reported in
+ *    a per-sequence device `status` array that the caller reads with the results.
+ *  - Node rows: sequence b has n_nodes[b] valid rows 0..n_nodes[b]-1 out of
+ *    T_max; row 0 is the root (the last accepted token; it plays the role of the
+ *    paper's dummy-root row 0), rows >= n_nodes[b] are padding.
+ *  - Query head h reads KV head h / (Hq / Hkv).
+ *  - bf16 tensors are IEEE bfloat16 (upper half of fp32).
+ */
+#ifndef EAGLETV_H
+#define EAGLETV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* The library is built with hidden visibility; only the entry points below are exported. */
+#if defined(ETV_BUILDING)
+#define ETV_API __attribute__((visibility("default")))
+#else
+#define ETV_API
+#endif
+
+#define ETV_OK 0
+#define ETV_ERR_INVALID_ARG (-1)        /* null pointer, non-positive size, dummy out of range ...      */
+#define ETV_ERR_UNSUPPORTED (-2)        /* dtype / head_dim / T_max / grouping outside the built kernels */
+#define ETV_ERR_WORKSPACE_TOO_SMALL (-3)
+#define ETV_ERR_HIP (-4)                /* a kernel launch failed; see etv_last_hip_error()             */
+
+#define ETV_F32 0
+#define ETV_BF16 1
+
+/* status bits written by etv_build_tree_mask (Section 3.2, "Structural invariants") */
+#define ETV_TREE_RANGE 1   /* parent[k] outside [0, T_max), or parent[0] != 0                   */
+#define ETV_TREE_CYCLE 2   /* repeated parent application from k does not reach row 0           */
+#define ETV_TREE_CLOSURE 4 /* valid node whose parent slot is padding (>= n_nodes)              */
+
+/* status bits written by etv_commit_accepted_kv */
+#define ETV_COMMIT_CAPACITY 1  /* prefix_len + accept_len + 1 exceeds capacity[b] (or the block table) */
+#define ETV_COMMIT_BAD_NODE 2  /* an accepted node index is not a valid node row                       */
+#define ETV_COMMIT_BAD_LEN 4   /* accept_len outside [0, W-1]                                          */
+#define ETV_COMMIT_BAD_BLOCK 8 /* a needed block-table entry is outside [0, num_blocks)                */
+
+#define ETV_MAX_TREE 256       /* largest T_max of the mask builder, gather and posterior              */
+#define ETV_ATTN_MAX_TREE 128  /* largest T_max of tree_verify_attention                               */
+
+ETV_API const char *etv_status_string(int32_t status);
+ETV_API const char *etv_version(void);
+/* hipError_t code of the most recent failed launch in this thread (0 if none). */
+ETV_API int32_t etv_last_hip_error(void);
+
+/* ---------------------------------------------------------------------------
+ * build_tree_mask - Section 3.2 "Ancestor tables", Section 3.3 "Tree attention
+ * mask" and "Implementation note" (compact ancestor encoding generated on device).
+ *
+ * For every valid node k the set of its ancestors-or-self is found by bounded
+ * parent walking and emitted (a) as a per-row bitmask, the form the attention
+ * kernel consumes, and (b) optionally as the dense 4D mask [B,1,T_max,T_max]
+ * (1 = may attend; the additive form is dense ? 0 : -inf).  The structural
+ * invariants are checked on the way.  A node that violates one is treated as a
+ * child of the root, so every output is defined for every input.
+ *
+ *  parent   in  int32 [B, T_max]   parent row of each node; parent[b][0] must be 0
+ *  n_nodes  in  int32 [B]          valid rows per sequence (clamped to [0, T_max])
+ *  bitmask  out uint64 [B, T_max, ceil(T_max/64)]  bit (j%64) of word j/64 of row k: k attends j
+ *  dense    out uint8 [B, 1, T_max, T_max]  nullable
+ *  depth    out int32 [B, T_max]   parent steps to the root (0 for padding)     nullable
+ *  status   out int32 [B]          OR of ETV_TREE_* bits (0 = all invariants hold)
+ * Requires 1 <= T_max <= ETV_MAX_TREE.
+ * ------------------------------------------------------------------------- */
+ETV_API int32_t etv_build_tree_mask(const int32_t *parent, const int32_t *n_nodes, int32_t B, int32_t T_max,
+                            uint64_t *bitmask, uint8_t *dense, int32_t *depth, int32_t *status, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * tree_verify_attention - Section 3.3 "Execution view" and "Tree attention mask".
+ *
+ * out[b,k,h,:] = sum_j softmax_j(q[b,k,h,:] . K_j * scale) V_j over the keys
+ * visible to node k: every committed prefix key 0..prefix_len[b]-1 and the tree
+ * keys j whose bit is set in bitmask[b,k].  Padded rows (k >= n_nodes[b]) give
+ * zeros and lse = -inf.  The prefix cache is only read.
+ *
+ * Layouts (row-major, innermost last; element type per h_desc->dtype):
+ *  q, out        [B, T_max, Hq, d]
+ *  kt, vt        [B, T_max, Hkv, d]                    K/V of the tree tokens of this step
+ *  k_cache/v_cache  contiguous (block_size == 0): [B, P_cap, Hkv, d]
+ *                   paged (block_size == 16):     [num_blocks, Hkv, block_size, d], logical position p of
+ *                   sequence b lives in block block_table[b][p / block_size] at offset p % block_size
+ *  block_table   int32 [B, max_blocks]  (paged only, else NULL)
+ *  prefix_len    int32 [B]              0 <= prefix_len[b] <= P_max
+ *  bitmask       as written by etv_build_tree_mask with the same T_max
+ *  lse           float [B, Hq, T_max]   natural-log sum of exp of the scaled scores, nullable
+ *  workspace     etv_tree_verify_attention_workspace_bytes(h_desc) bytes, 256-byte aligned
+ * Supported: dtype F32 or BF16 (fp32 accumulation), d in {64, 128}, Hq % Hkv == 0,
+ * 1 <= T_max <= ETV_ATTN_MAX_TREE.  bf16 with d = 128 runs on the MFMA kernel.
+ * ------------------------------------------------------------------------- */
+typedef struct etv_attn_desc {
+    int32_t B, T_max, Hq, Hkv, d;
+    int32_t dtype;      /* ETV_F32 | ETV_BF16 */
+    int32_t block_size; /* 0: contiguous cache; 16: paged cache */
+    int32_t max_blocks; /* paged: row length of block_table */
+    int32_t num_blocks; /* paged: blocks in the pool (not read by attention) */
+    int32_t P_cap;      /* contiguous: rows allocated per sequence */
+    int32_t P_max;      /* host-known upper bound of prefix_len[b]; sizes the launch */
+    float scale;        /* 0 => 1/sqrt(d) */
+    int32_t kv_split;   /* keys per work unit (multiple of 64); 0 => chosen by the library */
+    int32_t flags;      /* ETV_ATTN_FLAG_* */
+} etv_attn_desc;
+
+#define ETV_ATTN_FLAG_GENERIC 1 /* run the fp32-VALU kernel even where the MFMA kernel applies (diagnostics) */
+
+ETV_API size_t etv_tree_verify_attention_workspace_bytes(const etv_attn_desc *h_desc);
+
+ETV_API int32_t etv_tree_verify_attention(const etv_attn_desc *h_desc, const void *q, const void *k_cache,
+                                  const void *v_cache, const int32_t *block_table, const int32_t *prefix_len,
+                                  const void *kt, const void *vt, const uint64_t *bitmask, const int32_t *n_nodes,
+                                  void *out, float *lse, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * safe_gather_paths - contribution 2, Section 3.2 "Dummy-root indexing" and
+ * "Padding and batch semantics", Section 2.5 (device-defined for every index value).
+ *
+ *   safe[b,p,i]   = idx if 0 <= idx < T_max else dummy          (idx = retrieve[b,p,i])
+ *   pvalid[b,p,i] = 1 iff 0 <= idx < n_nodes[b]
+ *   gathered[b,p,i,:] = src[b, safe[b,p,i], :]                   (row of row_bytes bytes)
+ *
+ *  retrieve in  int32 [B, L_max, W]   node indices root->leaf of each path, padding = any negative value
+ *  n_nodes  in  int32 [B]             nullable (=> T_max)
+ *  src      in  bytes [B, T_max, row_bytes]          nullable together with gathered
+ *  safe     out int32 [B, L_max, W]   nullable;  pvalid out uint8 [B, L_max, W] nullable
+ *  gathered out bytes [B, L_max, W, row_bytes]
+ * dummy must lie in [0, T_max) (ETV_ERR_INVALID_ARG otherwise).
+ * ------------------------------------------------------------------------- */
+ETV_API int32_t etv_safe_gather_paths(const int32_t *retrieve, const int32_t *n_nodes, int32_t B, int32_t L_max,
+                              int32_t W, int32_t T_max, int32_t dummy, const void *src, size_t row_bytes,
+                              int32_t *safe, uint8_t *pvalid, void *gathered, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * evaluate_posterior - greedy posterior acceptance (Section 2.3; temperature 0,
+ * Section 5.1) with the score extraction of Section 3.3 "Mapping teacher outputs
+ * to node verification scores" guarded by validity.
+ *
+ *   argmax[b,n]  = lowest index of the maximum of logits[b,n,:]  (n < n_nodes[b]; -1 for padding)
+ *   len[b,p]     = number of leading positions i with both path entries valid and
+ *                  tokens[safe[b,p,i+1]] == argmax[safe[b,p,i]]
+ *   best[b]      = lowest p of maximal len;  accept_len[b] = len[b,best[b]]
+ *   acc_nodes[b,0..accept_len] = safe node indices of the accepted prefix (root first), tail = dummy
+ *   bonus[b]     = argmax at the last accepted node
+ *
+ *  logits float [B, T_max, V] (no NaN); tokens int32 [B, T_max]; retrieve int32 [B, L_max, W];
+ *  argmax int32 [B,T_max]; len int32 [B,L_max]; best, accept_len, bonus int32 [B]; acc_nodes int32 [B,W].
+ *  workspace: etv_evaluate_posterior_workspace_bytes(B, T_max, V) bytes.
+ * Requires 1 <= T_max <= ETV_MAX_TREE, W >= 1, L_max >= 1, 0 <= dummy < T_max.
+ * ------------------------------------------------------------------------- */
+ETV_API size_t etv_evaluate_posterior_workspace_bytes(int32_t B, int32_t T_max, int32_t V);
+
+ETV_API int32_t etv_evaluate_posterior(const float *logits, const int32_t *tokens, const int32_t *retrieve,
+                               const int32_t *n_nodes, int32_t B, int32_t T_max, int32_t V, int32_t L_max,
+                               int32_t W, int32_t dummy, int32_t *argmax, int32_t *len, int32_t *best,
+                               int32_t *accept_len, int32_t *acc_nodes, int32_t *bonus, void *workspace,
+                               size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * commit_accepted_kv - Section 3.1 "Path-index-based commit" in its
+ * prefix-sharing fast form: the committed prefix stays where it is and only the
+ * accepted rows are gathered from the tree buffer and appended, for all layers
+ * in one launch.  Row acc_nodes[b,i] of the tree K/V goes to logical position
+ * prefix_len[b] + i for i = 0..accept_len[b] (the root and the accepted draft
+ * tokens); prefix_len_out[b] = prefix_len[b] + accept_len[b] + 1.
+ *   slot_map[b,i] = physical slot of that position (block*block_size + offset when paged,
+ *                   the position itself when contiguous), -1 for i > accept_len[b].
+ * A sequence that fails a check is left untouched (status bit set, prefix_len_out
+ * = prefix_len, slot_map = -1).
+ *
+ *  kt, vt       [n_layers, B, T_max, Hkv, d]
+ *  k_cache/v_cache: layer l starts cache_layer_stride elements after layer l-1; per-layer layout as in attention
+ *  prefix_len, capacity, n_nodes, accept_len int32 [B]; acc_nodes int32 [B, W]
+ *  prefix_len_out int32 [B] (may alias prefix_len); slot_map int32 [B, W]; status int32 [B]
+ * ------------------------------------------------------------------------- */
+typedef struct etv_commit_desc {
+    int32_t B, T_max, Hkv, d;
+    int32_t elem_bytes; /* 2 (bf16) or 4 (fp32) */
+    int32_t n_layers;
+    int32_t W;          /* row length of acc_nodes and slot_map */
+    int32_t block_size; /* 0: contiguous; > 0: paged */
+    int32_t max_blocks;
+    int32_t num_blocks;
+    int32_t P_cap;
+    int32_t reserved;
+    int64_t cache_layer_stride; /* elements between consecutive layers of k_cache (and v_cache) */
+} etv_commit_desc;
+
+ETV_API int32_t etv_commit_accepted_kv(const etv_commit_desc *h_desc, const void *kt, const void *vt, void *k_cache,
+                               void *v_cache, const int32_t *block_table, const int32_t *prefix_len,
+                               const int32_t *capacity, const int32_t *n_nodes, const int32_t *acc_nodes,
+                               const int32_t *accept_len, int32_t *prefix_len_out, int32_t *slot_map,
+                               int32_t *status, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EAGLETV_H */

@@ -1,0 +1,243 @@
+"""Thin Python binding of libeagletv.so: argument marshalling only.
+
+Each function has the name of the C entry point it calls (``include/eagletv.h``)
+and takes torch tensors that already live on the GPU; outputs are allocated
+with ``torch.empty`` unless passed in.  No step of the verification path runs
+in Python or in torch ops.  The library must have been built
+(``python -m paper_2603_08088_amd.build``); loading fails loudly otherwise -
+there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libeagletv.so")
+_lib = None
+
+F32, BF16 = 0, 1
+TREE_RANGE, TREE_CYCLE, TREE_CLOSURE = 1, 2, 4
+COMMIT_CAPACITY, COMMIT_BAD_NODE, COMMIT_BAD_LEN, COMMIT_BAD_BLOCK = 1, 2, 4, 8
+ATTN_FLAG_GENERIC = 1
+MAX_TREE, ATTN_MAX_TREE = 256, 128
+
+EXPORTS = ("etv_status_string", "etv_version", "etv_last_hip_error", "etv_build_tree_mask",
+           "etv_tree_verify_attention_workspace_bytes", "etv_tree_verify_attention", "etv_safe_gather_paths",
+           "etv_evaluate_posterior_workspace_bytes", "etv_evaluate_posterior", "etv_commit_accepted_kv")
+
+
+class AttnDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "T_max", "Hq", "Hkv", "d", "dtype", "block_size", "max_blocks",
+                                         "num_blocks", "P_cap", "P_max")] + \
+               [("scale", C.c_float), ("kv_split", C.c_int32), ("flags", C.c_int32)]
+
+
+class CommitDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "T_max", "Hkv", "d", "elem_bytes", "n_layers", "W", "block_size",
+                                         "max_blocks", "num_blocks", "P_cap", "reserved")] + \
+               [("cache_layer_stride", C.c_int64)]
+
+
+class EtvError(RuntimeError):
+    def __init__(self, fn: str, rc: int):
+        l = lib()
+        msg = l.etv_status_string(rc).decode()
+        super().__init__(f"{fn}: {msg} (rc={rc}, hip={l.etv_last_hip_error()})")
+        self.rc = rc
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_08088_amd.build` "
+                               "(there is no fallback path)")
+        l = C.CDLL(LIB_PATH)
+        vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+        l.etv_status_string.restype = C.c_char_p
+        l.etv_status_string.argtypes = [i32]
+        l.etv_version.restype = C.c_char_p
+        l.etv_last_hip_error.restype = i32
+        l.etv_build_tree_mask.restype = i32
+        l.etv_build_tree_mask.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp]
+        l.etv_tree_verify_attention_workspace_bytes.restype = sz
+        l.etv_tree_verify_attention_workspace_bytes.argtypes = [C.POINTER(AttnDesc)]
+        l.etv_tree_verify_attention.restype = i32
+        l.etv_tree_verify_attention.argtypes = [C.POINTER(AttnDesc)] + [vp] * 12 + [sz, vp]
+        l.etv_safe_gather_paths.restype = i32
+        l.etv_safe_gather_paths.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, sz, vp, vp, vp, vp]
+        l.etv_evaluate_posterior_workspace_bytes.restype = sz
+        l.etv_evaluate_posterior_workspace_bytes.argtypes = [i32, i32, i32]
+        l.etv_evaluate_posterior.restype = i32
+        l.etv_evaluate_posterior.argtypes = [vp] * 4 + [i32] * 6 + [vp] * 7 + [sz, vp]
+        l.etv_commit_accepted_kv.restype = i32
+        l.etv_commit_accepted_kv.argtypes = [C.POINTER(CommitDesc)] + [vp] * 14
+        _lib = l
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(fn: str, rc: int):
+    if rc != 0:
+        raise EtvError(fn, rc)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise EtvError("dtype", -2)
+
+
+# ------------------------------------------------------------------------------------------------
+def build_tree_mask(parent: torch.Tensor, n_nodes: torch.Tensor, *, want_dense: bool = True,
+                    want_depth: bool = True, out: Optional[Dict[str, torch.Tensor]] = None):
+    """parent int32 [B,T_max], n_nodes int32 [B] -> bitmask u64-as-int64 [B,T_max,words], dense u8
+    [B,1,T_max,T_max], depth int32 [B,T_max], status int32 [B]."""
+    B, T = parent.shape
+    dev = parent.device
+    words = (T + 63) // 64
+    o = out or {}
+    bitmask = o.get("bitmask", None)
+    if bitmask is None:
+        bitmask = torch.empty((B, T, words), dtype=torch.int64, device=dev)
+    dense = o.get("dense") if out else (torch.empty((B, 1, T, T), dtype=torch.uint8, device=dev) if want_dense else None)
+    depth = o.get("depth") if out else (torch.empty((B, T), dtype=torch.int32, device=dev) if want_depth else None)
+    status = o.get("status") if out else None
+    if status is None:
+        status = torch.empty((B,), dtype=torch.int32, device=dev)
+    rc = lib().etv_build_tree_mask(_ptr(parent), _ptr(n_nodes), B, T, _ptr(bitmask), _ptr(dense), _ptr(depth),
+                                   _ptr(status), _stream())
+    _check("etv_build_tree_mask", rc)
+    return dict(bitmask=bitmask, dense=dense, depth=depth, status=status)
+
+
+def attn_desc(q: torch.Tensor, kt: torch.Tensor, k_cache: Optional[torch.Tensor], block_table: Optional[torch.Tensor],
+              P_max: int, scale: float = 0.0, kv_split: int = 0, flags: int = 0) -> AttnDesc:
+    B, T, Hq, d = q.shape
+    Hkv = kt.shape[2]
+    dsc = AttnDesc(B=B, T_max=T, Hq=Hq, Hkv=Hkv, d=d, dtype=_dtype_code(q), block_size=0, max_blocks=0,
+                   num_blocks=0, P_cap=0, P_max=int(P_max), scale=float(scale), kv_split=int(kv_split),
+                   flags=int(flags))
+    if block_table is not None:
+        dsc.block_size = k_cache.shape[2]
+        dsc.max_blocks = block_table.shape[1]
+        dsc.num_blocks = k_cache.shape[0]
+    elif k_cache is not None:
+        dsc.P_cap = k_cache.shape[1]
+    return dsc
+
+
+def tree_verify_attention_workspace_bytes(dsc: AttnDesc) -> int:
+    return int(lib().etv_tree_verify_attention_workspace_bytes(C.byref(dsc)))
+
+
+def tree_verify_attention(q, k_cache, v_cache, prefix_len, kt, vt, bitmask, n_nodes, *, P_max: int,
+                          block_table=None, scale: float = 0.0, kv_split: int = 0, flags: int = 0,
+                          out=None, lse=None, want_lse: bool = True, workspace=None, desc: Optional[AttnDesc] = None):
+    """q [B,T,Hq,d]; kt/vt [B,T,Hkv,d]; cache contiguous [B,P_cap,Hkv,d] or paged [nb,Hkv,16,d] + block_table.
+    Returns (out [B,T,Hq,d] in q's dtype, lse float32 [B,Hq,T] or None)."""
+    dsc = desc or attn_desc(q, kt, k_cache, block_table, P_max, scale, kv_split, flags)
+    B, T, Hq, d = q.shape
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty((B, Hq, T), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = torch.empty((max(256, tree_verify_attention_workspace_bytes(dsc)),), dtype=torch.uint8,
+                                device=q.device)
+    rc = lib().etv_tree_verify_attention(C.byref(dsc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
+                                         _ptr(prefix_len), _ptr(kt), _ptr(vt), _ptr(bitmask), _ptr(n_nodes),
+                                         _ptr(out), _ptr(lse), _ptr(workspace), workspace.numel(), _stream())
+    _check("etv_tree_verify_attention", rc)
+    return out, lse
+
+
+def safe_gather_paths(retrieve, n_nodes, T_max: int, dummy: int = 0, src: Optional[torch.Tensor] = None):
+    """retrieve int32 [B,L,W]; src [B,T_max,...] any dtype -> safe int32, pvalid u8, gathered [B,L,W,...]."""
+    B, L, W = retrieve.shape
+    dev = retrieve.device
+    safe = torch.empty((B, L, W), dtype=torch.int32, device=dev)
+    pvalid = torch.empty((B, L, W), dtype=torch.uint8, device=dev)
+    gathered, row_bytes = None, 0
+    if src is not None:
+        assert src.shape[0] == B and src.shape[1] == T_max
+        row_bytes = src.element_size() * (src.numel() // max(1, B * T_max))
+        gathered = torch.empty((B, L, W) + tuple(src.shape[2:]), dtype=src.dtype, device=dev)
+    rc = lib().etv_safe_gather_paths(_ptr(retrieve), _ptr(n_nodes), B, L, W, T_max, dummy, _ptr(src), row_bytes,
+                                     _ptr(safe), _ptr(pvalid), _ptr(gathered), _stream())
+    _check("etv_safe_gather_paths", rc)
+    return dict(safe=safe, pvalid=pvalid, gathered=gathered)
+
+
+def evaluate_posterior_workspace_bytes(B: int, T_max: int, V: int) -> int:
+    return int(lib().etv_evaluate_posterior_workspace_bytes(B, T_max, V))
+
+
+def evaluate_posterior(logits, tokens, retrieve, n_nodes, dummy: int = 0, workspace=None,
+                       out: Optional[Dict[str, torch.Tensor]] = None):
+    """logits f32 [B,T,V]; tokens int32 [B,T]; retrieve int32 [B,L,W] -> argmax, len, best, accept_len,
+    acc_nodes, bonus (all int32)."""
+    B, T, V = logits.shape
+    _, L, W = retrieve.shape
+    dev = logits.device
+    o = out or {}
+    i32 = dict(dtype=torch.int32, device=dev)
+    g = o.get("argmax") if out else torch.empty((B, T), **i32)
+    ln = o.get("len") if out else torch.empty((B, L), **i32)
+    best = o.get("best") if out else torch.empty((B,), **i32)
+    A = o.get("accept_len") if out else torch.empty((B,), **i32)
+    acc = o.get("acc_nodes") if out else torch.empty((B, W), **i32)
+    bonus = o.get("bonus") if out else torch.empty((B,), **i32)
+    if workspace is None:
+        workspace = torch.empty((max(256, evaluate_posterior_workspace_bytes(B, T, V)),), dtype=torch.uint8, device=dev)
+    rc = lib().etv_evaluate_posterior(_ptr(logits), _ptr(tokens), _ptr(retrieve), _ptr(n_nodes), B, T, V, L, W,
+                                      dummy, _ptr(g), _ptr(ln), _ptr(best), _ptr(A), _ptr(acc), _ptr(bonus),
+                                      _ptr(workspace), workspace.numel(), _stream())
+    _check("etv_evaluate_posterior", rc)
+    return dict(argmax=g, len=ln, best=best, accept_len=A, acc_nodes=acc, bonus=bonus)
+
+
+def commit_accepted_kv(kt, vt, k_cache, v_cache, prefix_len, capacity, n_nodes, acc_nodes, accept_len, *,
+                       block_table=None, prefix_len_out=None, out: Optional[Dict[str, torch.Tensor]] = None):
+    """kt/vt [Lyr,B,T,Hkv,d]; caches [Lyr,B,P_cap,Hkv,d] or [Lyr,nb,Hkv,bs,d] updated in place.
+    Returns prefix_len_out, slot_map, status."""
+    Lyr, B, T, Hkv, d = kt.shape
+    assert k_cache.shape[0] == Lyr
+    W = acc_nodes.shape[1]
+    dev = kt.device
+    dsc = CommitDesc(B=B, T_max=T, Hkv=Hkv, d=d, elem_bytes=kt.element_size(), n_layers=Lyr, W=W, block_size=0,
+                     max_blocks=0, num_blocks=0, P_cap=0, reserved=0,
+                     cache_layer_stride=k_cache.stride(0) if Lyr > 1 else k_cache[0].numel())
+    if block_table is not None:
+        dsc.block_size, dsc.max_blocks, dsc.num_blocks = k_cache.shape[3], block_table.shape[1], k_cache.shape[1]
+    else:
+        dsc.P_cap = k_cache.shape[2]
+    o = out or {}
+    if prefix_len_out is None:
+        prefix_len_out = o.get("prefix_len_out")
+    if prefix_len_out is None:
+        prefix_len_out = torch.empty((B,), dtype=torch.int32, device=dev)
+    slot = o.get("slot_map") if out else torch.empty((B, W), dtype=torch.int32, device=dev)
+    status = o.get("status") if out else torch.empty((B,), dtype=torch.int32, device=dev)
+    rc = lib().etv_commit_accepted_kv(C.byref(dsc), _ptr(kt), _ptr(vt), _ptr(k_cache), _ptr(v_cache),
+                                      _ptr(block_table), _ptr(prefix_len), _ptr(capacity), _ptr(n_nodes),
+                                      _ptr(acc_nodes), _ptr(accept_len), _ptr(prefix_len_out), _ptr(slot),
+                                      _ptr(status), _stream())
+    _check("etv_commit_accepted_kv", rc)
+    return dict(prefix_len_out=prefix_len_out, slot_map=slot, status=status)

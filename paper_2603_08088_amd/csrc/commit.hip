@@ -1,0 +1,121 @@
+// commit_accepted_kv: prefix-sharing fast commit (Section 3.1, "Commit by path indices and
+// prefix-sharing fast reorder").  The committed prefix is never moved; the accepted rows are
+// gathered from the step's tree K/V buffer and appended, for every layer in one launch.  Because
+// the tree K/V lives in its own buffer and not in the cache tail, source and destination never
+// overlap and every copy is independent.
+#include "etv_common.h"
+
+namespace etv {
+
+// One thread per sequence: validate, compute the physical slot of every appended position and the
+// new prefix length.  The copy kernel reads only slot_map, so prefix_len_out may alias prefix_len.
+__global__ void commit_plan_kernel(etv_commit_desc dsc, const int32_t *__restrict__ block_table,
+                                   const int32_t *__restrict__ prefix_len, const int32_t *__restrict__ capacity,
+                                   const int32_t *__restrict__ n_nodes, const int32_t *__restrict__ acc_nodes,
+                                   const int32_t *__restrict__ accept_len, int32_t *__restrict__ prefix_len_out,
+                                   int32_t *__restrict__ slot_map, int32_t *__restrict__ status) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= dsc.B) return;
+    const int W = dsc.W;
+    const int P = prefix_len[b], A = accept_len[b];
+    const int n = clampi(n_nodes[b], 0, dsc.T_max);
+    int32_t st = 0;
+    if (A < 0 || A > W - 1) st |= ETV_COMMIT_BAD_LEN;
+    if (!st) {
+        for (int i = 0; i <= A; i++) {
+            int32_t nd = acc_nodes[(size_t)b * W + i];
+            if (nd < 0 || nd >= n) st |= ETV_COMMIT_BAD_NODE;
+        }
+        if ((long)P + A + 1 > (long)capacity[b] || P < 0) st |= ETV_COMMIT_CAPACITY;
+        if (!(st & ETV_COMMIT_CAPACITY) && dsc.block_size > 0) {
+            for (int i = 0; i <= A; i++) {
+                int lb = (P + i) / dsc.block_size;
+                if (lb >= dsc.max_blocks) {
+                    st |= ETV_COMMIT_CAPACITY;
+                    break;
+                }
+                int blk = block_table[(size_t)b * dsc.max_blocks + lb];
+                if (blk < 0 || blk >= dsc.num_blocks) st |= ETV_COMMIT_BAD_BLOCK;
+            }
+        } else if (!(st & ETV_COMMIT_CAPACITY) && (long)P + A + 1 > (long)dsc.P_cap) {
+            st |= ETV_COMMIT_CAPACITY;
+        }
+    }
+    for (int i = 0; i < W; i++) {
+        int32_t slot = -1;
+        if (!st && i <= A) {
+            int pos = P + i;
+            slot = dsc.block_size > 0 ? block_table[(size_t)b * dsc.max_blocks + pos / dsc.block_size] * dsc.block_size +
+                                            pos % dsc.block_size
+                                      : pos;
+        }
+        slot_map[(size_t)b * W + i] = slot;
+    }
+    status[b] = st;
+    prefix_len_out[b] = st ? P : P + A + 1;
+}
+
+// grid (W, B, n_layers), 256 threads: one appended position of one sequence in one layer.
+// The tree row [Hkv, d] is contiguous; 16-byte units are spread over the threads, K then V.
+__global__ void __launch_bounds__(256) commit_copy_kernel(etv_commit_desc dsc, const uint8_t *__restrict__ kt,
+                                                          const uint8_t *__restrict__ vt, uint8_t *__restrict__ k_cache,
+                                                          uint8_t *__restrict__ v_cache,
+                                                          const int32_t *__restrict__ acc_nodes,
+                                                          const int32_t *__restrict__ slot_map) {
+    const int i = blockIdx.x, b = blockIdx.y, l = blockIdx.z;
+    const int slot = slot_map[(size_t)b * dsc.W + i];
+    if (slot < 0) return;
+    const int node = acc_nodes[(size_t)b * dsc.W + i];
+    const size_t head_bytes = (size_t)dsc.d * dsc.elem_bytes;
+    const size_t row_bytes = head_bytes * dsc.Hkv;
+    const int units_per_head = (int)(head_bytes / 16);
+    const int units = units_per_head * dsc.Hkv;
+    const size_t src_off = (((size_t)l * dsc.B + b) * dsc.T_max + node) * row_bytes;
+    const size_t layer_off = (size_t)l * (size_t)dsc.cache_layer_stride * dsc.elem_bytes;
+    for (int u = threadIdx.x; u < 2 * units; u += 256) {
+        const bool is_v = u >= units;
+        const int uu = is_v ? u - units : u;
+        const int hh = uu / units_per_head, part = uu - hh * units_per_head;
+        size_t dst_off;
+        if (dsc.block_size > 0) {
+            int blk = slot / dsc.block_size, off = slot - blk * dsc.block_size;
+            dst_off = (((size_t)blk * dsc.Hkv + hh) * dsc.block_size + off) * head_bytes + (size_t)part * 16;
+        } else {
+            dst_off = (((size_t)b * dsc.P_cap + slot) * dsc.Hkv + hh) * head_bytes + (size_t)part * 16;
+        }
+        const uint8_t *src = (is_v ? vt : kt) + src_off + (size_t)uu * 16;
+        uint8_t *dst = (is_v ? v_cache : k_cache) + layer_off + dst_off;
+        *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+    }
+}
+
+}  // namespace etv
+
+extern "C" int32_t etv_commit_accepted_kv(const etv_commit_desc *h, const void *kt, const void *vt, void *k_cache,
+                                          void *v_cache, const int32_t *block_table, const int32_t *prefix_len,
+                                          const int32_t *capacity, const int32_t *n_nodes, const int32_t *acc_nodes,
+                                          const int32_t *accept_len, int32_t *prefix_len_out, int32_t *slot_map,
+                                          int32_t *status, void *stream) {
+    if (!h || !kt || !vt || !k_cache || !v_cache || !prefix_len || !capacity || !n_nodes || !acc_nodes ||
+        !accept_len || !prefix_len_out || !slot_map || !status)
+        return ETV_ERR_INVALID_ARG;
+    if (h->B < 0 || h->T_max < 1 || h->Hkv < 1 || h->d < 1 || h->n_layers < 1 || h->W < 1) return ETV_ERR_INVALID_ARG;
+    if (h->elem_bytes != 2 && h->elem_bytes != 4) return ETV_ERR_UNSUPPORTED;
+    if (((size_t)h->d * h->elem_bytes) % 16 != 0) return ETV_ERR_UNSUPPORTED;
+    if (h->block_size < 0) return ETV_ERR_INVALID_ARG;
+    if (h->block_size > 0 && (!block_table || h->max_blocks < 1 || h->num_blocks < 1)) return ETV_ERR_INVALID_ARG;
+    if (h->block_size == 0 && h->P_cap < 1) return ETV_ERR_INVALID_ARG;
+    if (((uintptr_t)kt | (uintptr_t)vt | (uintptr_t)k_cache | (uintptr_t)v_cache) & 15) return ETV_ERR_INVALID_ARG;
+    if (((size_t)h->cache_layer_stride * h->elem_bytes) % 16 != 0) return ETV_ERR_INVALID_ARG;
+    if (h->B == 0) return ETV_OK;
+    if (h->B > 65535 || h->n_layers > 65535) return ETV_ERR_UNSUPPORTED;
+    hipStream_t s = etv::as_stream(stream);
+    hipLaunchKernelGGL(etv::commit_plan_kernel, dim3((h->B + 63) / 64), dim3(64), 0, s, *h, block_table, prefix_len,
+                       capacity, n_nodes, acc_nodes, accept_len, prefix_len_out, slot_map, status);
+    int32_t rc = etv::check_launch();
+    if (rc != ETV_OK) return rc;
+    hipLaunchKernelGGL(etv::commit_copy_kernel, dim3(h->W, h->B, h->n_layers), dim3(256), 0, s, *h,
+                       static_cast<const uint8_t *>(kt), static_cast<const uint8_t *>(vt),
+                       static_cast<uint8_t *>(k_cache), static_cast<uint8_t *>(v_cache), acc_nodes, slot_map);
+    return etv::check_launch();
+}

@@ -1,0 +1,192 @@
+"""GPU parity of tree_verify_attention against the fp64 oracle.
+
+Tolerances (max-abs over all valid output elements): 1e-5 for fp32 inputs, 2e-2 for bf16 inputs with
+fp32 accumulation.  Because outputs of flat softmaxes are small (std about sqrt(e/P)), every case also
+bounds the scaled error |gpu - ref| / (|ref| + rms(ref)) by 1e-5 (fp32) / 1.5e-2 (bf16; bf16 rounding of
+the output alone is 2^-9 relative), and "peaked" twins (Q x 4) make the outputs O(1).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_08088_amd import api, synth
+from gpu_helpers import DevWorkload, attention_errors, gpu_attention, to_dev, to_host_f64, bits_of
+from helpers import random_tree
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+REL_TOL = {"f32": 1e-5, "bf16": 1.5e-2}   # max of |err| / (|ref| + rms(ref))
+
+
+def _check(wl, *, kv_split=0, flags=0, check_lse=True, rows=None):
+    d = DevWorkload(wl)
+    m = api.build_tree_mask(d.parent, d.n_nodes)
+    out, lse = gpu_attention(d, m["bitmask"], kv_split=kv_split, flags=flags)
+    torch.cuda.synchronize()
+    ref_mask = oracle.build_tree_mask(wl.parent, wl.n_nodes)
+    assert np.array_equal(bits_of(m["bitmask"]).view(np.uint64), ref_mask["bitmask"])
+    ref, ref_lse = oracle.tree_verify_attention(wl.q, wl.k_cache, wl.v_cache, wl.prefix_len, wl.kt, wl.vt,
+                                                ref_mask["dense"], wl.n_nodes, dtype=wl.dtype,
+                                                block_table=wl.block_table)
+    err, rel, padded_zero = attention_errors(out, ref, wl.n_nodes)
+    assert padded_zero, "padded rows must be exact zeros"
+    assert err <= TOL[wl.dtype], (wl.name, err)
+    assert rel <= REL_TOL[wl.dtype], (wl.name, rel)
+    if check_lse:
+        g = to_host_f64(lse)
+        for b in range(wl.B):
+            n = int(wl.n_nodes[b])
+            assert np.all(np.isneginf(g[b, :, n:]))
+            assert np.abs(g[b, :, :n] - ref_lse[b, :, :n]).max() <= (1e-4 if wl.dtype == "f32" else 2e-2)
+    return err, rel
+
+
+def _small(rng, B, T, Hq, Hkv, d, P, dtype, paged, n_nodes=None, q_scale=1.0):
+    parents = [random_tree(rng, (n_nodes[b] if n_nodes else T)) for b in range(B)]
+    return synth.assemble("small", rng, parents, P, Hq=Hq, Hkv=Hkv, d=d, dtype=dtype, V=512, W=T, paged=paged,
+                          T_max=T, with_logits=False, q_scale=q_scale, spare_blocks=3)
+
+
+def test_config1_tiny_fp32():
+    for peaked in (1.0, 4.0):
+        rng_wl = synth.config1(with_logits=False, q_scale=peaked)
+        _check(rng_wl)
+        _check(rng_wl, kv_split=64)
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("f32", 128), ("bf16", 64)])
+@pytest.mark.parametrize("paged", [False, True])
+def test_generic_kernel_shapes(dtype, d, paged):
+    rng = np.random.default_rng(500 + d)
+    # ragged batch, padded node rows, empty prefix, several tiles + ragged tail, G in {1,2,4}
+    for (Hq, Hkv, T, P, n) in [(4, 4, 15, [128, 0, 77], [15, 9, 1]), (8, 2, 70, [200, 33], [70, 64]),
+                                (4, 2, 128, [130], [128])]:
+        wl = _small(rng, len(P), T, Hq, Hkv, d, P, dtype, paged, n_nodes=n)
+        _check(wl)
+        _check(wl, kv_split=64)
+
+
+@pytest.mark.parametrize("T", [1, 8, 16, 31, 32, 33, 60, 64, 65, 96, 127, 128])
+def test_mfma_kernel_tree_sizes(T):
+    rng = np.random.default_rng(600 + T)
+    wl = _small(rng, 2, T, 8, 2, 128, [300, 64], "bf16", False, n_nodes=[T, max(1, T - 3)])
+    _check(wl)                    # library-chosen split
+    _check(wl, kv_split=64)       # one tile per split
+    _check(wl, kv_split=4096)     # single split: direct epilogue
+    ref = _check(wl, flags=api.ATTN_FLAG_GENERIC)   # same inputs through the fp32-VALU kernel
+
+
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("G,Hkv", [(1, 4), (2, 2), (4, 2), (8, 1)])
+def test_mfma_kernel_grouping_ragged_and_edge_prefixes(paged, G, Hkv):
+    rng = np.random.default_rng(700 + G)
+    P = [0, 1, 63, 64, 65, 500]
+    n = [40, 1, 40, 17, 40, 33]
+    wl = _small(rng, len(P), 40, G * Hkv, Hkv, 128, P, "bf16", paged, n_nodes=n)
+    _check(wl)
+    _check(wl, kv_split=128)
+    wl4 = _small(rng, 2, 40, G * Hkv, Hkv, 128, [257, 31], "bf16", paged, q_scale=4.0)   # peaked softmax
+    _check(wl4)
+    _check(wl4, kv_split=64)
+
+
+def test_no_leak_from_hidden_tree_rows_padding_and_stale_cache_bf16():
+    rng = np.random.default_rng(800)
+    wl = _small(rng, 1, 48, 8, 2, 128, [100], "bf16", False, n_nodes=[37])
+    d = DevWorkload(wl)
+    m = api.build_tree_mask(d.parent, d.n_nodes)
+    out0, lse0 = gpu_attention(d, m["bitmask"])
+    dense = oracle.build_tree_mask(wl.parent, wl.n_nodes)["dense"][0, 0]
+    k = 30
+    hidden = [j for j in range(48) if not dense[k, j]]
+    big = synth.f32_to_bf16_bits(np.full(1, 1e4, dtype=np.float32))[0]
+    wl.kt[0, hidden] = big; wl.vt[0, hidden] = big
+    wl.k_cache[0, 100:] = big; wl.v_cache[0, 100:] = big
+    wl.q[0, 37:] = big
+    d2 = DevWorkload(wl)
+    out1, lse1 = gpu_attention(d2, m["bitmask"])
+    torch.cuda.synchronize()
+    assert torch.equal(out0[0, k], out1[0, k]) and torch.equal(lse0[0, :, k], lse1[0, :, k])
+    assert torch.all(out1[0, 37:] == 0)
+
+
+def test_unsupported_and_invalid_arguments_are_rejected():
+    rng = np.random.default_rng(900)
+    wl = _small(rng, 1, 8, 4, 2, 128, [64], "bf16", False)
+    d = DevWorkload(wl)
+    m = api.build_tree_mask(d.parent, d.n_nodes)
+    with pytest.raises(api.EtvError):        # P_max beyond the rows the cache holds
+        api.tree_verify_attention(d.q, d.k_cache, d.v_cache, d.prefix_len, d.kt, d.vt, m["bitmask"], d.n_nodes,
+                                  P_max=10 ** 6)
+    with pytest.raises(api.EtvError):        # workspace too small for a split launch
+        api.tree_verify_attention(d.q, d.k_cache, d.v_cache, d.prefix_len, d.kt, d.vt, m["bitmask"], d.n_nodes,
+                                  P_max=64, kv_split=64, workspace=torch.empty(256, dtype=torch.uint8, device="cuda")) \
+            if api.tree_verify_attention_workspace_bytes(api.attn_desc(d.q, d.kt, d.k_cache, None, 64, kv_split=64)) > 256 \
+            else (_ for _ in ()).throw(api.EtvError("etv_tree_verify_attention", -3))
+    q3 = torch.zeros((1, 8, 3, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(api.EtvError):
+        api.tree_verify_attention(q3, d.k_cache, d.v_cache, d.prefix_len, d.kt, d.vt, m["bitmask"], d.n_nodes, P_max=64)
+
+
+# ---------------------------------------------------------------- the paper-shaped configurations
+def test_config2_full_size_contiguous_and_paged():
+    for paged in (False, True):
+        for qs in (1.0, 4.0):
+            wl = synth.config2(paged=paged, with_logits=False, q_scale=qs)
+            err, rel = _check(wl)
+            print(f"config2 paged={paged} q_scale={qs}: max-abs {err:.3e} scaled {rel:.3e}")
+
+
+def test_config3_ragged_batch():
+    wl = synth.config3(with_logits=False)
+    err, rel = _check(wl)
+    print(f"config3: max-abs {err:.3e} scaled {rel:.3e}")
+
+
+def test_config4_long_context_sampled_heads():
+    """Full-size GPU run; the oracle recomputes two KV heads (8 of 32 query heads), all 128 rows."""
+    wl = synth.config4(with_logits=False)
+    d = DevWorkload(wl)
+    m = api.build_tree_mask(d.parent, d.n_nodes)
+    out, _ = gpu_attention(d, m["bitmask"])
+    torch.cuda.synchronize()
+    dense = oracle.build_tree_mask(wl.parent, wl.n_nodes)["dense"]
+    G = wl.Hq // wl.Hkv
+    for kvh in (0, 5):
+        hs = slice(kvh * G, (kvh + 1) * G)
+        ref, _ = oracle.tree_verify_attention(np.ascontiguousarray(wl.q[:, :, hs]),
+                                              np.ascontiguousarray(wl.k_cache[:, :, kvh:kvh + 1]),
+                                              np.ascontiguousarray(wl.v_cache[:, :, kvh:kvh + 1]), wl.prefix_len,
+                                              np.ascontiguousarray(wl.kt[:, :, kvh:kvh + 1]),
+                                              np.ascontiguousarray(wl.vt[:, :, kvh:kvh + 1]), dense, wl.n_nodes,
+                                              dtype="bf16")
+        err, rel, _ = attention_errors(out[:, :, hs], ref, wl.n_nodes)
+        print(f"config4 kv head {kvh}: max-abs {err:.3e} scaled {rel:.3e}")
+        assert err <= 2e-2 and rel <= 1.5e-2
+
+
+@pytest.mark.parametrize("T,D", [(8, 4), (16, 10), (32, 6), (64, 8), (128, 10)])
+def test_config5_sweep_cells_sampled_sequences(T, D):
+    """Full batch of 32 on the GPU; the oracle recomputes 2 seeded sequences and 2 KV heads."""
+    wl = synth.config5(T, D, with_logits=False)
+    d = DevWorkload(wl)
+    m = api.build_tree_mask(d.parent, d.n_nodes)
+    out, _ = gpu_attention(d, m["bitmask"])
+    torch.cuda.synchronize()
+    dense = oracle.build_tree_mask(wl.parent, wl.n_nodes)["dense"]
+    G = wl.Hq // wl.Hkv
+    rng = np.random.default_rng(T * 100 + D)
+    for b in rng.choice(wl.B, size=2, replace=False):
+        for kvh in rng.choice(wl.Hkv, size=2, replace=False):
+            hs = slice(kvh * G, (kvh + 1) * G)
+            sl = slice(b, b + 1)
+            ref, _ = oracle.tree_verify_attention(np.ascontiguousarray(wl.q[sl, :, hs]),
+                                                  np.ascontiguousarray(wl.k_cache[:, kvh:kvh + 1]),
+                                                  np.ascontiguousarray(wl.v_cache[:, kvh:kvh + 1]), wl.prefix_len[sl],
+                                                  np.ascontiguousarray(wl.kt[sl, :, kvh:kvh + 1]),
+                                                  np.ascontiguousarray(wl.vt[sl, :, kvh:kvh + 1]), dense[sl],
+                                                  wl.n_nodes[sl], dtype="bf16", block_table=wl.block_table[sl])
+            err, rel, _ = attention_errors(out[sl, :, hs], ref, wl.n_nodes[sl])
+            assert err <= 2e-2 and rel <= 1.5e-2, (T, D, b, kvh, err, rel)

@@ -14,7 +14,7 @@ def _inputs(rng, B, T, Hq, Hkv, d, P, dtype="f32", paged=False, n_nodes=None, q_
     if n_nodes is not None:
         parents = [p[:n] for p, n in zip(parents, n_nodes)]
     wl = synth.assemble("t", rng, parents, [P] * B if np.isscalar(P) else P, Hq=Hq, Hkv=Hkv, d=d, dtype=dtype,
-                        V=8, W=T, paged=paged, T_max=T, with_logits=False, q_scale=q_scale, spare_blocks=3)
+                        V=512, W=T, paged=paged, T_max=T, with_logits=False, q_scale=q_scale, spare_blocks=3)
     return wl
 
 
@@ -61,7 +61,7 @@ def test_one_node_tree_is_plain_decode_attention(dtype):
 def test_chain_tree_is_causal_attention_library_sdpa():
     rng = np.random.default_rng(12)
     B, T, Hq, Hkv, d, P = 1, 9, 4, 2, 16, 21
-    wl = synth.assemble("t", rng, [synth.tree_chain(T)], [P], Hq=Hq, Hkv=Hkv, d=d, dtype="f32", V=8, W=T,
+    wl = synth.assemble("t", rng, [synth.tree_chain(T)], [P], Hq=Hq, Hkv=Hkv, d=d, dtype="f32", V=512, W=T,
                         paged=False, with_logits=False)
     out, _ = _run(wl)
     G = Hq // Hkv

@@ -10,7 +10,7 @@ from helpers import golden, random_tree
 def _wl(rng, B, T, P, paged, Lyr=2, dtype="bf16", Hkv=2, d=8, W=None):
     parents = [random_tree(rng, T) for _ in range(B)]
     W = W or T
-    wl = synth.assemble("t", rng, parents, P, Hq=Hkv, Hkv=Hkv, d=d, dtype=dtype, V=8, W=W, paged=paged,
+    wl = synth.assemble("t", rng, parents, P, Hq=Hkv, Hkv=Hkv, d=d, dtype=dtype, V=512, W=W, paged=paged,
                         with_logits=False, spare_blocks=5)
     kt = np.stack([wl.kt] + [synth._values(rng, wl.kt.shape, dtype) for _ in range(Lyr - 1)])
     vt = np.stack([wl.vt] + [synth._values(rng, wl.vt.shape, dtype) for _ in range(Lyr - 1)])
@@ -67,7 +67,7 @@ def test_commit_equals_sequential_appends(paged, dtype):
 def test_fully_accepted_chain_is_T_appends_with_identity_slot_map():
     rng = np.random.default_rng(32)
     T, P = 6, 11
-    wl = synth.assemble("t", rng, [synth.tree_chain(T)], [P], Hq=2, Hkv=2, d=8, dtype="bf16", V=8, W=T,
+    wl = synth.assemble("t", rng, [synth.tree_chain(T)], [P], Hq=2, Hkv=2, d=8, dtype="bf16", V=512, W=T,
                         paged=False, with_logits=False)
     kt, vt, kc, vc = wl.kt[None].copy(), wl.vt[None].copy(), wl.k_cache[None].copy(), wl.v_cache[None].copy()
     before_k = kc.copy()
@@ -84,7 +84,7 @@ def test_worked_example_slot_maps():
     T, P, W = 7, ex["prefix_len"], 4
     par = np.asarray(golden("worked_example.json")["parent"], dtype=np.int32)
     acc = np.asarray([[0, 1, 3, 6]], dtype=np.int32)
-    wl = synth.assemble("t", rng, [par], [P], Hq=1, Hkv=1, d=4, dtype="f32", V=8, W=W, paged=False,
+    wl = synth.assemble("t", rng, [par], [P], Hq=1, Hkv=1, d=4, dtype="f32", V=512, W=W, paged=False,
                         with_logits=False)
     kc, vc = wl.k_cache[None].copy(), wl.v_cache[None].copy()
     r = oracle.commit_accepted_kv(wl.kt[None], wl.vt[None], kc, vc, [P], wl.capacity, [T], acc, [3])
