@@ -1,0 +1,271 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verify step on one MI355X.
+
+One step = one pass of the whole verification path over one batch of synthetic input:
+  build_tree_mask -> tree_verify_attention for each of the model's layers -> safe_gather_paths ->
+  evaluate_posterior -> commit_accepted_kv over all layers (one launch),
+with every input already resident in HBM.  The step is captured once into a HIP graph per cache
+set and replayed; cache sets are rotated so that consecutive steps stream K/V from HBM, not from
+the 256 MB memory-side cache.  Prints ONE JSON line (metric: tree-verify tokens/s).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5_T<T>_D<D>] [--layers L]
+                  [--no-graph] [--skip-cpu] [--kv-split N]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--kv-split", type=int, default=0)
+    ap.add_argument("--sets", type=int, default=0, help="cache sets to rotate over (0 = enough to exceed 640 MB)")
+    return ap.parse_args()
+
+
+def make_host_workload(name):
+    from paper_2603_08088_amd import synth
+    if name == "c2":
+        return synth.config2(with_cache=False), "7B-class GQA verify step: B=1, 32/8 heads, d=128, bf16, P=2048, 60-node tree"
+    if name == "c2_paged":
+        return synth.config2(paged=True, with_cache=False), "config 2 with a paged prefix cache"
+    if name == "c3":
+        return synth.config3(with_cache=False), "ragged batch: B=8, P~U[512,8192], paged, 60-node trees"
+    if name == "c4":
+        return synth.config4(with_cache=False), "long context: B=1, P=32768, 128-node tree"
+    m = re.fullmatch(r"c5_T(\d+)_D(\d+)", name)
+    if m:
+        return synth.config5(int(m.group(1)), int(m.group(2)), with_cache=False), \
+            f"budget sweep cell: B=32, P=4096 paged, T={m.group(1)}, depth {m.group(2)}"
+    raise SystemExit(f"unknown workload {name}")
+
+
+class Step:
+    """Device state of one workload and the launch sequence of a step."""
+
+    def __init__(self, wl, layers, nsets, kv_split):
+        import numpy as np
+        import torch
+        from paper_2603_08088_amd import api
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from gpu_helpers import to_dev
+        self.api, self.torch, self.wl, self.L = api, torch, wl, layers
+        dev = "cuda:0"
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(26030808)
+        B, T, Hq, Hkv, d = wl.B, wl.T_max, wl.Hq, wl.Hkv, wl.d
+        self.parent, self.n_nodes = to_dev(wl.parent), to_dev(wl.n_nodes)
+        self.tokens, self.retrieve = to_dev(wl.tokens), to_dev(wl.retrieve)
+        self.prefix_len, self.capacity = to_dev(wl.prefix_len), to_dev(wl.capacity)
+        self.block_table = to_dev(wl.block_table)
+        self.logits = to_dev(wl.logits)
+        self.P_max = int(wl.prefix_len.max())
+        bf = torch.bfloat16
+
+        def rnd(*shape):
+            return torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(bf)
+        self.q = rnd(layers, B, T, Hq, d)
+        self.kt, self.vt = rnd(layers, B, T, Hkv, d), rnd(layers, B, T, Hkv, d)
+        cshape = (wl.num_blocks, Hkv, 16, d) if wl.paged else (B, wl.P_cap, Hkv, d)
+        per_set = 2 * layers * int(np.prod(cshape)) * 2
+        self.nsets = nsets if nsets > 0 else max(1, -(-640 * 2 ** 20 // per_set))
+        self.kc = [torch.empty((layers,) + cshape, dtype=bf, device=dev) for _ in range(self.nsets)]
+        self.vc = [torch.empty((layers,) + cshape, dtype=bf, device=dev) for _ in range(self.nsets)]
+        for s in range(self.nsets):
+            for l in range(layers):   # layer by layer keeps the fp32 staging buffer small
+                self.kc[s][l].copy_(torch.randn(cshape, generator=gen, device=dev, dtype=torch.float32))
+                self.vc[s][l].copy_(torch.randn(cshape, generator=gen, device=dev, dtype=torch.float32))
+        self.cache_bytes = per_set * self.nsets
+        # outputs and workspaces, allocated once
+        i32 = dict(dtype=torch.int32, device=dev)
+        words = (T + 63) // 64
+        L_max, W = wl.retrieve.shape[1], wl.W
+        self.mask_out = dict(bitmask=torch.empty((B, T, words), dtype=torch.int64, device=dev),
+                             dense=torch.empty((B, 1, T, T), dtype=torch.uint8, device=dev),
+                             depth=torch.empty((B, T), **i32), status=torch.empty((B,), **i32))
+        self.out = torch.empty((layers, B, T, Hq, d), dtype=bf, device=dev)
+        self.desc = api.attn_desc(self.q[0], self.kt[0], self.kc[0][0], self.block_table, self.P_max, 0.0, kv_split)
+        self.ws = torch.empty((max(256, api.tree_verify_attention_workspace_bytes(self.desc)),), dtype=torch.uint8,
+                              device=dev)
+        self.tokens3 = self.tokens.reshape(B, T, 1)
+        self.gather_out = dict(safe=torch.empty((B, L_max, W), **i32),
+                               pvalid=torch.empty((B, L_max, W), dtype=torch.uint8, device=dev),
+                               gathered=torch.empty((B, L_max, W, 1), **i32))
+        self.post_out = dict(argmax=torch.empty((B, T), **i32), len=torch.empty((B, L_max), **i32),
+                             best=torch.empty((B,), **i32), accept_len=torch.empty((B,), **i32),
+                             acc_nodes=torch.empty((B, W), **i32), bonus=torch.empty((B,), **i32))
+        self.post_ws = torch.empty((max(256, api.evaluate_posterior_workspace_bytes(B, T, wl.V)),),
+                                   dtype=torch.uint8, device=dev)
+        self.commit_out = dict(prefix_len_out=torch.empty((B,), **i32), slot_map=torch.empty((B, W), **i32),
+                               status=torch.empty((B,), **i32))
+
+    def attention_layers(self, s):
+        api = self.api
+        for l in range(self.L):
+            api.tree_verify_attention(self.q[l], self.kc[s][l], self.vc[s][l], self.prefix_len, self.kt[l],
+                                      self.vt[l], self.mask_out["bitmask"], self.n_nodes, P_max=self.P_max,
+                                      block_table=self.block_table, out=self.out[l], want_lse=False,
+                                      workspace=self.ws, desc=self.desc)
+
+    def run(self, s):
+        api = self.api
+        api.build_tree_mask(self.parent, self.n_nodes, out=self.mask_out)
+        self.attention_layers(s)
+        api.safe_gather_paths(self.retrieve, self.n_nodes, self.wl.T_max, 0, self.tokens3, out=self.gather_out)
+        api.evaluate_posterior(self.logits, self.tokens, self.retrieve, self.n_nodes, 0, workspace=self.post_ws,
+                               out=self.post_out)
+        # the new prefix length goes to its own buffer so that every timed step sees the same prefix
+        api.commit_accepted_kv(self.kt, self.vt, self.kc[s], self.vc[s], self.prefix_len, self.capacity,
+                               self.n_nodes, self.post_out["acc_nodes"], self.post_out["accept_len"],
+                               block_table=self.block_table, out=self.commit_out)
+
+    def capture(self, fn):
+        torch = self.torch
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()                      # warm up outside capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            fn()
+        return g
+
+
+def attention_algorithmic(wl):
+    """Algorithmic bytes and flops of one attention launch (one layer): prefix K/V read once, tree K/V,
+    Q read and O written; 4*Hq*T*(P+T)*d flops."""
+    e = 2 if wl.dtype == "bf16" else 4
+    by = fl = 0
+    for b in range(wl.B):
+        P, T = int(wl.prefix_len[b]), int(wl.n_nodes[b])
+        by += 2 * P * wl.Hkv * wl.d * e + 2 * T * wl.Hkv * wl.d * e + 2 * T * wl.Hq * wl.d * e
+        fl += 4 * wl.Hq * T * (P + T) * wl.d
+    return by, fl
+
+
+def cpu_baseline(wl_name, layers):
+    """The oracle as it stands, timed on the host cores over one whole step of the same workload shape
+    (the layer loop re-runs the oracle attention on one layer's host data: time does not depend on values)."""
+    import numpy as np
+    import oracle
+    from paper_2603_08088_amd import synth
+    if wl_name == "c2":
+        wl, att_layers, note = synth.config2(), layers, f"one full step of config 2: mask + {layers} attention layers + gather + posterior + commit over {layers} layers"
+    else:
+        wl, _ = make_host_workload(wl_name)
+        return None
+    kt, vt = np.broadcast_to(wl.kt, (layers,) + wl.kt.shape).copy(), np.broadcast_to(wl.vt, (layers,) + wl.vt.shape).copy()
+    kc = np.broadcast_to(wl.k_cache, (layers,) + wl.k_cache.shape).copy()
+    vc = np.broadcast_to(wl.v_cache, (layers,) + wl.v_cache.shape).copy()
+    t0 = time.perf_counter()
+    m = oracle.build_tree_mask(wl.parent, wl.n_nodes)
+    for _ in range(att_layers):
+        oracle.tree_verify_attention(wl.q, wl.k_cache, wl.v_cache, wl.prefix_len, wl.kt, wl.vt, m["dense"],
+                                     wl.n_nodes, dtype=wl.dtype, block_table=wl.block_table, want_lse=False)
+    oracle.safe_gather_paths(wl.retrieve, wl.n_nodes, wl.T_max, 0, wl.tokens.reshape(wl.B, wl.T_max, 1))
+    p = oracle.evaluate_posterior(wl.logits, wl.tokens, wl.retrieve, wl.n_nodes)
+    oracle.commit_accepted_kv(kt, vt, kc, vc, wl.prefix_len, wl.capacity, wl.n_nodes, p["acc_nodes"], p["accept_len"],
+                              block_table=wl.block_table)
+    secs = time.perf_counter() - t0
+    return {"value": float(wl.n_nodes.sum()) / secs, "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": note, "seconds": secs}
+
+
+def main():
+    a = parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        raise SystemExit(2)
+    import numpy as np
+    import torch
+    from paper_2603_08088_amd import api
+    api.lib()   # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    wl, desc_text = make_host_workload(a.workload)
+    st = Step(wl, a.layers, a.sets, a.kv_split)
+    tokens_per_step = int(wl.n_nodes.sum())
+
+    if a.no_graph:
+        runners = [(lambda s=s: st.run(s)) for s in range(st.nsets)]
+    else:
+        graphs = [st.capture(lambda s=s: st.run(s)) for s in range(st.nsets)]
+        runners = [g.replay for g in graphs]
+    for i in range(a.warmup):
+        runners[i % st.nsets]()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        runners[i % st.nsets]()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / a.steps
+
+    # sanity of the step's integer results against what the generator planted
+    accept = st.post_out["accept_len"].cpu().numpy().tolist()
+    assert accept == [d for _, d in wl.planted], (accept, wl.planted)
+    assert int(st.commit_out["status"].abs().sum().item()) == 0 and int(st.mask_out["status"].abs().sum().item()) == 0
+
+    # dominant kernel: one tree_verify_attention launch per layer.  Time L launches back to back between
+    # HIP events on the launch stream (captured as a graph of attention launches only).
+    att = [st.capture(lambda s=s: st.attention_layers(s)) for s in range(st.nsets)] if not a.no_graph else None
+    reps = max(3, min(50, a.steps // 4))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(3):
+        (att[i % st.nsets].replay() if att else st.attention_layers(i % st.nsets))
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(reps):
+        (att[i % st.nsets].replay() if att else st.attention_layers(i % st.nsets))
+    e1.record()
+    torch.cuda.synchronize()
+    att_us = e0.elapsed_time(e1) * 1e3 / (reps * a.layers)
+    by, fl = attention_algorithmic(wl)
+    hbm_t, mfma_t = by / (HBM_PEAK_GBS * 1e9), fl / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if hbm_t >= mfma_t:
+        roof = {"bound": "hbm", "achieved": by / (att_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": fl / (att_us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    tpath = os.path.join(ROOT, "profiles", f"attention_hbm_traffic_{a.workload}.json")
+    if os.path.exists(tpath):
+        roof["traffic"] = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    roof.update({"kernel": "tree_verify_attention (one layer: split-KV partial kernel + combine)",
+                 "avg_launch_us": att_us, "algorithmic_bytes": by, "algorithmic_flops": fl,
+                 "hbm_gbs": by / (att_us * 1e-6) / 1e9, "mfma_tflops": fl / (att_us * 1e-6) / 1e12})
+
+    cpu = None if a.skip_cpu else cpu_baseline(a.workload, a.layers)
+    line = {
+        "metric": "tree-verify tokens/s (batch x tree nodes)", "value": tokens_per_step / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{a.workload}: {desc_text}", "layers": a.layers, "tokens_per_step": tokens_per_step,
+                   "launch": "eager" if a.no_graph else "hip-graph replay", "cache_sets": st.nsets,
+                   "cache_bytes": st.cache_bytes, "kv_split": a.kv_split},
+        "roofline": roof, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -168,17 +168,21 @@ def tree_verify_attention(q, k_cache, v_cache, prefix_len, kt, vt, bitmask, n_no
     return out, lse
 
 
-def safe_gather_paths(retrieve, n_nodes, T_max: int, dummy: int = 0, src: Optional[torch.Tensor] = None):
+def safe_gather_paths(retrieve, n_nodes, T_max: int, dummy: int = 0, src: Optional[torch.Tensor] = None,
+                      out: Optional[Dict[str, torch.Tensor]] = None):
     """retrieve int32 [B,L,W]; src [B,T_max,...] any dtype -> safe int32, pvalid u8, gathered [B,L,W,...]."""
     B, L, W = retrieve.shape
     dev = retrieve.device
-    safe = torch.empty((B, L, W), dtype=torch.int32, device=dev)
-    pvalid = torch.empty((B, L, W), dtype=torch.uint8, device=dev)
+    o = out or {}
+    safe = o.get("safe") if out else torch.empty((B, L, W), dtype=torch.int32, device=dev)
+    pvalid = o.get("pvalid") if out else torch.empty((B, L, W), dtype=torch.uint8, device=dev)
     gathered, row_bytes = None, 0
     if src is not None:
         assert src.shape[0] == B and src.shape[1] == T_max
         row_bytes = src.element_size() * (src.numel() // max(1, B * T_max))
-        gathered = torch.empty((B, L, W) + tuple(src.shape[2:]), dtype=src.dtype, device=dev)
+        gathered = o.get("gathered") if out else None
+        if gathered is None:
+            gathered = torch.empty((B, L, W) + tuple(src.shape[2:]), dtype=src.dtype, device=dev)
     rc = lib().etv_safe_gather_paths(_ptr(retrieve), _ptr(n_nodes), B, L, W, T_max, dummy, _ptr(src), row_bytes,
                                      _ptr(safe), _ptr(pvalid), _ptr(gathered), _stream())
     _check("etv_safe_gather_paths", rc)

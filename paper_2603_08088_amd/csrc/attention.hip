@@ -25,6 +25,8 @@ struct AttnParams {
     int B, T_max, Hq, Hkv, G, d, block_size, max_blocks, P_cap, P_max, words;
     int chunk;   // prefix keys per split, multiple of 64
     int nsplit;  // splits the launch provides; sequence b uses max(1, ceil(P_b / chunk)) of them
+    // partial results, split-major so that one workgroup writes one contiguous region:
+    //   part_o [B][nsplit][Hq][T_max][d], part_m / part_l [B][nsplit][Hq][T_max]
     int pairs;   // mfma kernel: (head-in-group, row chunk) pairs per KV head
     int wgp;     // mfma kernel: workgroups per (b, kv head, split) = ceil(pairs / 4)
     float scale_log2;
@@ -34,6 +36,9 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ int seq_prefix_len(const AttnParams &p, int b) { return clampi(p.prefix_len[b], 0, p.P_max); }
 __device__ __forceinline__ int seq_nsplit(const AttnParams &p, int P) { return max(1, (P + p.chunk - 1) / p.chunk); }
+__device__ __forceinline__ size_t part_row(const AttnParams &p, int b, int s, int h, int k) {
+    return (((size_t)b * p.nsplit + s) * p.Hq + h) * p.T_max + k;
+}
 
 // element offset of prefix row `key` of KV head kvh (contiguous or paged cache)
 __device__ __forceinline__ size_t prefix_row_offset(const AttnParams &p, int b, int kvh, int key) {
@@ -183,7 +188,7 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(AttnParams p) {
         for (int i = 0; i < DPL; i++) store_elem<T>(out, orow + lane + 64 * i, o[i] * inv);
         if (p.lse && lane == 0) p.lse[((size_t)b * p.Hq + h) * p.T_max + k] = (m + log2f(l)) * kLn2;
     } else {
-        const size_t pr = (((size_t)b * p.Hq + h) * p.T_max + k) * p.nsplit + s;
+        const size_t pr = part_row(p, b, s, h, k);
 #pragma unroll
         for (int i = 0; i < DPL; i++) p.part_o[pr * D + lane + 64 * i] = o[i];
         if (lane == 0) {
@@ -209,15 +214,35 @@ __global__ void __launch_bounds__(D) attn_combine_kernel(AttnParams p) {
         return;
     }
     const int nvalid = seq_nsplit(p, seq_prefix_len(p, b));
-    const size_t pr = lrow * p.nsplit;
+    const size_t pr0 = part_row(p, b, 0, h, k);
+    const size_t sstride = (size_t)p.Hq * p.T_max;  // rows between consecutive splits
     float M = -INFINITY;
-    for (int s = 0; s < nvalid; s++) M = fmaxf(M, p.part_m[pr + s]);
+    for (int s0 = 0; s0 < nvalid; s0 += 8) {
+        float ms[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) ms[u] = (s0 + u < nvalid) ? p.part_m[pr0 + (size_t)(s0 + u) * sstride] : -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 8; u++) M = fmaxf(M, ms[u]);
+    }
     float L = 0.f, acc = 0.f;
-    for (int s = 0; s < nvalid; s++) {
-        float ms = p.part_m[pr + s];
-        float w = (ms == -INFINITY) ? 0.f : exp2f(ms - M);
-        L = fmaf(w, p.part_l[pr + s], L);
-        acc = fmaf(w, p.part_o[(pr + s) * D + c], acc);
+    for (int s0 = 0; s0 < nvalid; s0 += 8) {  // eight independent loads in flight per thread
+        float ms[8], ls[8], os[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const bool ok = s0 + u < nvalid;
+            const size_t r = pr0 + (size_t)(ok ? s0 + u : 0) * sstride;
+            ms[u] = ok ? p.part_m[r] : -INFINITY;
+            ls[u] = p.part_l[r];
+            os[u] = p.part_o[r * D + c];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            if (ms[u] != -INFINITY) {  // absent or empty split: its l/O may be uninitialised memory
+                const float w = exp2f(ms[u] - M);
+                L = fmaf(w, ls[u], L);
+                acc = fmaf(w, os[u], acc);
+            }
+        }
     }
     store_elem<T>(out, orow + c, acc / L);
     if (p.lse && c == 0) p.lse[lrow] = (M + log2f(L)) * kLn2;
@@ -226,9 +251,19 @@ __global__ void __launch_bounds__(D) attn_combine_kernel(AttnParams p) {
 // ----------------------------------------------------------------------------------------------
 // MFMA kernel (bf16, d = 128).
 //
-// Work unit: (split, KV head x row group, sequence).  A workgroup has 4 wavefronts; wavefront w owns one
-// (query head, row chunk) pair = 32*MT query rows of one head, and all 4 share the K/V tiles of their
-// KV head through LDS, so each prefix K/V byte is fetched from HBM once per G*T query rows.
+// Work unit: (split, KV head x row group, sequence).  A workgroup has NW wavefronts (8, or 4 for small
+// trees); wavefront w owns one (query head, 32-row chunk) pair and all of them share the K/V tiles of
+// their KV head through LDS, so each prefix K/V byte is fetched from HBM once per G*T query rows.  Two
+// wavefronts are resident per SIMD: while one runs the softmax on the vector ALU the other feeds the
+// matrix cores.
+//
+// K/V tiles (64 keys x 256 B each) travel HBM -> LDS with asynchronous direct-to-LDS loads
+// (global_load_lds_dwordx4: no registers, completion tracked by vmcnt) into a ring of NS stages, so
+// NS-1 tiles (32 KiB each) are in flight per workgroup while one is being consumed; one workgroup
+// barrier per tile.  A direct-to-LDS load writes lane i's 16 bytes at (base + 16 i), so rows cannot be
+// padded; instead the 16-byte chunk c of key row r is stored at chunk position c ^ f(r) with
+// f(r) = ((r & 3) << 1) | ((r >> 2) & 1), which spreads both the 16-byte K reads (8 consecutive rows, same
+// chunk) and the 8-byte transpose reads of V (4 consecutive rows x 32 B) over all LDS banks.
 //
 // Per 64-key tile and wavefront (32x32x16 MFMA, 64-lane layouts: A/B operand lane = (row|col l%32,
 // 8 contraction values at 8*(l/32)); accumulator lane = (col l%32, rows 8*(i/4) + 4*(l/32) + i%4)):
@@ -245,12 +280,13 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(4))) const int32_t *const_i32_ptr;
 
-constexpr int KT = 64;          // keys per tile
-constexpr int K_STRIDE = 272;   // LDS bytes per K row: 256 + 16 (row-to-row bank rotation for 16-byte reads)
-constexpr int V_STRIDE = 288;   // LDS bytes per V row: 256 + 32 (bank rotation for the 8-byte transpose reads)
-constexpr int LDS_K_BYTES = KT * K_STRIDE;
-constexpr int LDS_V_BYTES = KT * V_STRIDE;
+constexpr int KT = 64;                      // keys per tile
+constexpr int ROW_BYTES = 256;              // one K or V row of a KV head (d = 128, bf16)
+constexpr int TILE_BYTES = KT * ROW_BYTES;  // 16 KiB
+constexpr int STAGE_BYTES = 2 * TILE_BYTES; // K tile then V tile
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     f32x2 v = {a, b};
@@ -258,16 +294,231 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     return __builtin_bit_cast(uint32_t, r);
 }
 
-template <int MT>
-__global__ void __launch_bounds__(256) attn_mfma_kernel(AttnParams p) {
+// 16 bytes per lane from global memory straight into LDS at (lds_addr + 16 * lane); asynchronous.
+__device__ __forceinline__ void async_load16(const void *gptr, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
+// wait until at most N of this wavefront's vector-memory loads are outstanding (N < 64)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+__device__ __forceinline__ int swz_of_row(int r) { return ((r & 3) << 1) | ((r >> 2) & 1); }
+
+extern __shared__ __attribute__((aligned(1024))) uint8_t attn_smem[];
+
+// Asynchronous loads of one 64-key K/V tile into ring stage (ti % NS).  A tile is 16 chunk pairs of
+// 1 KiB (4 key rows of K, the same 4 rows of V).  Wavefront w issues pairs w, w+NW, ...; in a chunk lane i
+// fetches key row 4j + i/16 and the 16-byte piece that belongs at chunk position i%16 of that row.
+template <int NW>
+struct TileLoader {
+    static constexpr int U = 16 / NW;  // chunk pairs per wavefront and tile
+    const uint8_t *kc, *vc, *kt, *vt;
+    const int32_t *bt;
+    size_t row_stride, seq_off, blk_stride, head_off;
+    uint32_t smem_addr;
+    int wave, l_row, l_pos, k0, k1, npt, n;
+    size_t lane_off_contig[U];   // per-lane part of the source offset, contiguous cache
+    uint32_t lane_off_paged[U];  // same, paged cache (within one block of one head)
+};
+
+// full prefix tile (all 64 keys exist): straight-line address arithmetic
+template <int NW, int NS, bool PAGED>
+__device__ __forceinline__ void issue_full_tile(const TileLoader<NW> &ld, int ti) {
+    constexpr int U = TileLoader<NW>::U;
+    const int base = ld.k0 + ti * KT;
+    const uint32_t stage = ld.smem_addr + (uint32_t)(ti % NS) * STAGE_BYTES;
+    if (PAGED) {
+        int blk[U];
+#pragma unroll
+        for (int u = 0; u < U; u++)  // scalar loads: the block table is read-only for the kernel
+            blk[u] = ((const_i32_ptr)(uintptr_t)ld.bt)[(base >> 4) + ((ld.wave + NW * u) >> 2)];
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const int j = ld.wave + NW * u;
+            const size_t off = (size_t)blk[u] * ld.blk_stride + ld.head_off + ld.lane_off_paged[u];
+            async_load16(ld.kc + off, stage + j * 1024);
+            async_load16(ld.vc + off, stage + TILE_BYTES + j * 1024);
+        }
+    } else {
+        const size_t tile_off = ld.seq_off + (size_t)base * ld.row_stride;
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const int j = ld.wave + NW * u;
+            const size_t off = tile_off + ld.lane_off_contig[u];
+            async_load16(ld.kc + off, stage + j * 1024);
+            async_load16(ld.vc + off, stage + TILE_BYTES + j * 1024);
+        }
+    }
+}
+
+// ragged last prefix tile or tree tile: rows past the end re-read the last valid row (masked later)
+template <int NW, int NS>
+__device__ __forceinline__ void issue_edge_tile(const TileLoader<NW> &ld, int ti) {
+    constexpr int U = TileLoader<NW>::U;
+    const bool tree = ti >= ld.npt;
+    const int base = tree ? (ti - ld.npt) * KT : ld.k0 + ti * KT;
+    const int last = (tree ? ld.n : ld.k1) - 1;
+    const uint32_t stage = ld.smem_addr + (uint32_t)(ti % NS) * STAGE_BYTES;
+    const uint8_t *ksrc = tree ? ld.kt : ld.kc;
+    const uint8_t *vsrc = tree ? ld.vt : ld.vc;
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+        const int j = ld.wave + NW * u;
+        const int r_in = 4 * j + ld.l_row;
+        const int key = min(base + r_in, last);
+        size_t off;
+        if (tree) {
+            off = (size_t)key * ld.row_stride;
+        } else if (ld.bt) {
+            // the logical block is the same for the whole chunk (its rows are clamped into one block)
+            const int lb = __builtin_amdgcn_readfirstlane(min(base + 4 * j, last) >> 4);
+            const int blk = ((const_i32_ptr)(uintptr_t)ld.bt)[lb];
+            off = (size_t)blk * ld.blk_stride + ld.head_off + (size_t)(key & 15) * ROW_BYTES;
+        } else {
+            off = ld.seq_off + (size_t)key * ld.row_stride;
+        }
+        off += (ld.l_pos ^ swz_of_row(r_in)) * 16;
+        async_load16(ksrc + off, stage + j * 1024);
+        async_load16(vsrc + off, stage + TILE_BYTES + j * 1024);
+    }
+}
+
+// LDS view of one staged tile plus the per-lane fragment offsets (bytes) that do not depend on the tile.
+struct TileView {
+    const uint8_t *lk, *lv;
+    int krow;          // K fragment row offset: row (lane%32) of key block 0; block 1 is 32 rows further
+    int ksw;           // swizzle term of that row (the same for row + 32)
+    int vrow, vsw, vchunk, vsub;  // V transpose-read row within a 16-key step, its swizzle, chunk, sub-offset
+    int hh;            // lane / 32
+};
+
+// How far the running reference of a row may lag behind its true maximum (log2 units) before the
+// accumulators are rescaled: exp2 arguments stay <= kLazy, so P <= 256 and nothing overflows, and the
+// rescale of the O registers (which live in accumulator registers and cost three instructions each to
+// touch) becomes rare after the first tiles.
+constexpr float kLazy = 8.0f;
+
+// One 64-key tile for one wavefront (32 query rows).  MASKED: key kin of the tile is visible to the
+// lane's row iff bit kin of `vis`.
+template <bool MASKED>
+__device__ __forceinline__ void process_tile(const TileView &tv, const bf16x8 (&qreg)[8], f32x16 (&oacc)[4],
+                                             float &m_run, float &l_run, float scale_log2, uint64_t vis) {
+    // ---- S^T = K Q^T: two independent accumulator chains (keys 0..31 and 32..63)
+    f32x16 s0, s1;
+#pragma unroll
+    for (int i = 0; i < 16; i++) { s0[i] = 0.f; s1[i] = 0.f; }
+    {
+        bf16x8 ka[8], kb[8];
+#pragma unroll
+        for (int kk = 0; kk < 8; kk++) {
+            const int col = (((2 * kk + tv.hh) ^ tv.ksw) << 4);
+            ka[kk] = *reinterpret_cast<const bf16x8 *>(tv.lk + tv.krow + col);
+            kb[kk] = *reinterpret_cast<const bf16x8 *>(tv.lk + tv.krow + 32 * ROW_BYTES + col);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 8; kk++) {
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qreg[kk], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[kk], qreg[kk], s1, 0, 0, 0);
+        }
+    }
+    // V^T fragments of the first 32 keys fly while the softmax runs
+    bf16x8 vf[2][4];
+    auto load_v = [&](int kb) {
+#pragma unroll
+        for (int st = 0; st < 2; st++) {
+            const uint8_t *vr = tv.lv + (32 * kb + 16 * st + tv.vrow) * ROW_BYTES + tv.vsub;
+#pragma unroll
+            for (int db = 0; db < 4; db++) {
+                const int cpos = ((4 * db + tv.vchunk) ^ tv.vsw) << 4;
+                const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vr + cpos));
+                const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vr + 8 * ROW_BYTES + cpos));
+                const bf16x4 a0 = __builtin_bit_cast(bf16x4, v0), a1 = __builtin_bit_cast(bf16x4, v1);
+                vf[st][db] = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        }
+    };
+    load_v(0);
+
+    // ---- mask, running reference, P^T = exp2(S^T * scale - m) packed to bf16
+    if (MASKED) {
+        const uint32_t lo = (uint32_t)(vis >> (4 * tv.hh)), hi = (uint32_t)(vis >> (32 + 4 * tv.hh));
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int bit = 8 * (i >> 2) + (i & 3);
+            s0[i] = ((lo >> bit) & 1u) ? s0[i] : -INFINITY;
+            s1[i] = ((hi >> bit) & 1u) ? s1[i] : -INFINITY;
+        }
+    }
+    float rmax = fmaxf(s0[0], s1[0]);
+#pragma unroll
+    for (int i = 1; i < 16; i++) rmax = fmaxf(rmax, fmaxf(s0[i], s1[i]));
+    rmax = fmaxf(rmax, __shfl_xor(rmax, 32));
+    const float tmax = rmax * scale_log2;  // scale_log2 > 0
+    const bool lift = tmax > m_run + kLazy;  // also true for the first visible keys (reference -inf)
+    if (__any(lift)) {
+        // only the rows that need it move their reference; the others multiply by exactly 1, so a row's
+        // arithmetic never depends on what the other rows of the wavefront see
+        const float m_new = lift ? tmax : m_run;
+        const float alpha = lift ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < 4; db++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) oacc[db][i] *= alpha;
+    }
+    const float neg_m = (MASKED && m_run == -INFINITY) ? 0.f : -m_run;
+    bf16x8 pf[2][2];
+    float psum = 0.f;
+    {
+        uint32_t pk0[8], pk1[8];
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            const float a0 = __builtin_amdgcn_exp2f(fmaf(s0[i], scale_log2, neg_m));
+            const float a1 = __builtin_amdgcn_exp2f(fmaf(s0[i + 1], scale_log2, neg_m));
+            const float b0 = __builtin_amdgcn_exp2f(fmaf(s1[i], scale_log2, neg_m));
+            const float b1 = __builtin_amdgcn_exp2f(fmaf(s1[i + 1], scale_log2, neg_m));
+            psum += (a0 + a1) + (b0 + b1);
+            pk0[i >> 1] = pack_bf16x2(a0, a1);
+            pk1[i >> 1] = pack_bf16x2(b0, b1);
+        }
+        const uint4 l0 = {pk0[0], pk0[1], pk0[2], pk0[3]}, h0 = {pk0[4], pk0[5], pk0[6], pk0[7]};
+        const uint4 l1 = {pk1[0], pk1[1], pk1[2], pk1[3]}, h1 = {pk1[4], pk1[5], pk1[6], pk1[7]};
+        pf[0][0] = __builtin_bit_cast(bf16x8, l0); pf[0][1] = __builtin_bit_cast(bf16x8, h0);
+        pf[1][0] = __builtin_bit_cast(bf16x8, l1); pf[1][1] = __builtin_bit_cast(bf16x8, h1);
+    }
+    l_run += psum;
+
+    // ---- O^T += V^T P^T: four independent accumulator chains (d blocks)
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+        bf16x8 va[2][4];
+#pragma unroll
+        for (int st = 0; st < 2; st++)
+#pragma unroll
+            for (int db = 0; db < 4; db++) va[st][db] = vf[st][db];
+        if (kb == 0) load_v(1);  // the second half's fragments fly during the first half's products
+#pragma unroll
+        for (int st = 0; st < 2; st++)
+#pragma unroll
+            for (int db = 0; db < 4; db++)
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[st][db], pf[kb][st], oacc[db], 0, 0, 0);
+    }
+}
+
+template <int NW, int NS, bool PAGED>
+__global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     constexpr int D = 128;
-    __shared__ __attribute__((aligned(16))) uint8_t lds_k[LDS_K_BYTES];
-    __shared__ __attribute__((aligned(16))) uint8_t lds_v[LDS_V_BYTES];
+    constexpr int LPW = 2 * TileLoader<NW>::U;  // direct-to-LDS loads each wavefront issues per tile
+    uint8_t *const smem = attn_smem;
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)attn_smem;
 
     const int s = blockIdx.x;
     const int kvh = blockIdx.y / p.wgp, wg = blockIdx.y % p.wgp;
     const int b = blockIdx.z;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c32 = lane & 31, hh = lane >> 5;
 
     const int n = clampi(p.n_nodes[b], 0, p.T_max);
@@ -276,231 +527,139 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnParams p) {
     if (s >= nvalid) return;  // uniform over the workgroup
     const bool direct = (p.nsplit == 1);
 
-    const int pair = wg * 4 + wave;
+    const int pair = wg * NW + wave;
     const bool active = pair < p.pairs;
     const int g = active ? pair % p.G : 0;
     const int rc = active ? pair / p.G : 0;
     const int h = kvh * p.G + g;
-    const int row0 = rc * 32 * MT;
-
-    const uint16_t *qp = static_cast<const uint16_t *>(p.q);
-    // Q as B operand: lane holds query row (row0 + 32*mt + c32), d values 16*kk + 8*hh .. +7
-    bf16x8 qreg[MT][8];
-    uint64_t mbits[MT][2];
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        const int kq = row0 + 32 * mt + c32;
-        const bool rv = active && kq < n;
-        mbits[mt][0] = 0;
-        mbits[mt][1] = 0;
-        if (rv) {
-            const uint64_t *mrow = p.bitmask + ((size_t)b * p.T_max + kq) * p.words;
-            mbits[mt][0] = mrow[0];
-            if (p.words > 1) mbits[mt][1] = mrow[1];
-        }
-#pragma unroll
-        for (int kk = 0; kk < 8; kk++) {
-            uint4 v = {0, 0, 0, 0};
-            if (rv) v = *reinterpret_cast<const uint4 *>(qp + (((size_t)b * p.T_max + kq) * p.Hq + h) * D + 16 * kk + 8 * hh);
-            qreg[mt][kk] = __builtin_bit_cast(bf16x8, v);
-        }
-    }
-
-    f32x16 oacc[MT][4];
-    float m_run[MT], l_run[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        m_run[mt] = -INFINITY;
-        l_run[mt] = 0.f;
-#pragma unroll
-        for (int db = 0; db < 4; db++)
-#pragma unroll
-            for (int i = 0; i < 16; i++) oacc[mt][db][i] = 0.f;
-    }
+    const int kq = rc * 32 + c32;  // the lane's query row
 
     const int k0 = s * p.chunk, k1 = min(P, k0 + p.chunk);
-    const int npt = (k1 > k0) ? (k1 - k0 + KT - 1) / KT : 0;
-    const int ntt = (s == nvalid - 1) ? (n + KT - 1) / KT : 0;
+    const int nfull = (k1 > k0) ? (k1 - k0) / KT : 0;               // full prefix tiles
+    const int npt = (k1 > k0) ? (k1 - k0 + KT - 1) / KT : 0;        // prefix tiles incl. a ragged last one
+    const int ntt = (s == nvalid - 1) ? (n + KT - 1) / KT : 0;      // tree tiles
     const int nt = npt + ntt;
 
-    const uint8_t *kc = static_cast<const uint8_t *>(p.k_cache), *vc = static_cast<const uint8_t *>(p.v_cache);
-    const uint8_t *ktp = static_cast<const uint8_t *>(p.kt), *vtp = static_cast<const uint8_t *>(p.vt);
-
-    uint4 kreg[4], vreg[4];
-    // global -> registers for tile `ti`: thread handles 16-byte part (c & 15) of key (c >> 4), c = tid + 256 j
-    auto load_tile = [&](int ti) {
-        const bool tree = ti >= npt;
-        const int base = tree ? (ti - npt) * KT : k0 + ti * KT;
-        const int limit = tree ? n : k1;
+    TileLoader<NW> ld;
+    ld.kc = static_cast<const uint8_t *>(p.k_cache); ld.vc = static_cast<const uint8_t *>(p.v_cache);
+    ld.kt = static_cast<const uint8_t *>(p.kt) + ((size_t)b * p.T_max * p.Hkv + kvh) * ROW_BYTES;
+    ld.vt = static_cast<const uint8_t *>(p.vt) + ((size_t)b * p.T_max * p.Hkv + kvh) * ROW_BYTES;
+    ld.bt = PAGED ? p.block_table + (size_t)b * p.max_blocks : nullptr;
+    ld.row_stride = (size_t)p.Hkv * ROW_BYTES;
+    ld.seq_off = ((size_t)b * p.P_cap * p.Hkv + kvh) * ROW_BYTES;   // contiguous cache: row 0 of (b, kvh)
+    ld.blk_stride = (size_t)p.Hkv * 16 * ROW_BYTES;                  // paged cache: one block, all heads
+    ld.head_off = (size_t)kvh * 16 * ROW_BYTES;
+    ld.smem_addr = smem_addr; ld.wave = wave; ld.l_row = lane >> 4; ld.l_pos = lane & 15;
+    ld.k0 = k0; ld.k1 = k1; ld.npt = npt; ld.n = n;
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const int c = tid + 256 * j;
-            const int key = base + (c >> 4);
-            uint4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-            if (key < limit) {
-                const size_t off = (tree ? tree_row_offset(p, b, kvh, key) : prefix_row_offset(p, b, kvh, key)) * 2 +
-                                   (size_t)(c & 15) * 16;
-                kv = *reinterpret_cast<const uint4 *>((tree ? ktp : kc) + off);
-                vv = *reinterpret_cast<const uint4 *>((tree ? vtp : vc) + off);
-            }
-            kreg[j] = kv;
-            vreg[j] = vv;
-        }
-    };
-    auto store_tile = [&]() {
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const int c = tid + 256 * j;
-            *reinterpret_cast<uint4 *>(lds_k + (c >> 4) * K_STRIDE + (c & 15) * 16) = kreg[j];
-            *reinterpret_cast<uint4 *>(lds_v + (c >> 4) * V_STRIDE + (c & 15) * 16) = vreg[j];
-        }
+    for (int u = 0; u < TileLoader<NW>::U; u++) {
+        const int r_in = 4 * (wave + NW * u) + ld.l_row;
+        const int col = (ld.l_pos ^ swz_of_row(r_in)) * 16;
+        ld.lane_off_contig[u] = (size_t)r_in * ld.row_stride + col;
+        ld.lane_off_paged[u] = (uint32_t)((r_in & 15) * ROW_BYTES + col);
+    }
+    auto issue = [&](int ti) {
+        if (ti < nfull) issue_full_tile<NW, NS, PAGED>(ld, ti);
+        else issue_edge_tile<NW, NS>(ld, ti);
     };
 
-    if (nt > 0) load_tile(0);
-    for (int ti = 0; ti < nt; ti++) {
-        __syncthreads();  // previous tile fully consumed
-        store_tile();
-        __syncthreads();
-        if (ti + 1 < nt) load_tile(ti + 1);  // in flight during the compute below
+    // prologue: fill NS-1 stages, then fetch Q and the mask row while those loads fly
+    for (int ti = 0; ti < NS - 1 && ti < nt; ti++) issue(ti);
 
-        const bool tree = ti >= npt;
-        const int base = tree ? (ti - npt) * KT : k0 + ti * KT;
-        const int limit = tree ? n : k1;
+    const uint16_t *qp = static_cast<const uint16_t *>(p.q);
+    // Q as B operand: lane holds query row kq, d values 16*kk + 8*hh .. +7
+    bf16x8 qreg[8];
+    uint64_t mbits0 = 0, mbits1 = 0;
+    const bool rv = active && kq < n;
+    if (rv) {
+        const uint64_t *mrow = p.bitmask + ((size_t)b * p.T_max + kq) * p.words;
+        mbits0 = mrow[0];
+        if (p.words > 1) mbits1 = mrow[1];
+    }
+#pragma unroll
+    for (int kk = 0; kk < 8; kk++) {
+        uint4 v = {0, 0, 0, 0};
+        if (rv) v = *reinterpret_cast<const uint4 *>(qp + (((size_t)b * p.T_max + kq) * p.Hq + h) * D + 16 * kk + 8 * hh);
+        qreg[kk] = __builtin_bit_cast(bf16x8, v);
+    }
 
-        // ---- S^T = K Q^T
-        f32x16 sacc[2][MT];
+    f32x16 oacc[4];
+    float m_run = -INFINITY, l_run = 0.f;
 #pragma unroll
-        for (int kb = 0; kb < 2; kb++)
+    for (int db = 0; db < 4; db++)
 #pragma unroll
-            for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-                for (int i = 0; i < 16; i++) sacc[kb][mt][i] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < 8; kk++) {
-#pragma unroll
-            for (int kb = 0; kb < 2; kb++) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(lds_k + (32 * kb + c32) * K_STRIDE + (16 * kk + 8 * hh) * 2);
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++)
-                    sacc[kb][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[mt][kk], sacc[kb][mt], 0, 0, 0);
-            }
-        }
+        for (int i = 0; i < 16; i++) oacc[db][i] = 0.f;
 
-        // ---- mask + online softmax (per query column), P^T packed to bf16
-        bf16x8 pfrag[2][MT][2];
-        const bool need_mask = tree || (base + KT > limit);
-#pragma unroll
-        for (int mt = 0; mt < MT; mt++) {
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-                for (int i = 0; i < 16; i++) {
-                    float t = sacc[kb][mt][i] * p.scale_log2;
-                    if (need_mask) {
-                        const int kin = 32 * kb + 8 * (i >> 2) + 4 * hh + (i & 3);
-                        bool vis;
-                        if (tree) {
-                            const int j = base + kin;  // < 128
-                            vis = (mbits[mt][j >> 6] >> (j & 63)) & 1ull;
-                        } else {
-                            vis = (base + kin) < limit;
-                        }
-                        t = vis ? t : -INFINITY;
-                    }
-                    sacc[kb][mt][i] = t;
-                    tmax = fmaxf(tmax, t);
-                }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            const float m_new = fmaxf(m_run[mt], tmax);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - m_use);
-            float psum = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; kb++) {
-                uint32_t pk[8];
-#pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(sacc[kb][mt][i] - m_use);
-                    const float p1 = __builtin_amdgcn_exp2f(sacc[kb][mt][i + 1] - m_use);
-                    psum += p0 + p1;
-                    pk[i >> 1] = pack_bf16x2(p0, p1);
-                }
-                uint4 lo = {pk[0], pk[1], pk[2], pk[3]}, hi = {pk[4], pk[5], pk[6], pk[7]};
-                pfrag[kb][mt][0] = __builtin_bit_cast(bf16x8, lo);
-                pfrag[kb][mt][1] = __builtin_bit_cast(bf16x8, hi);
-            }
-            l_run[mt] = l_run[mt] * alpha + psum;
-            m_run[mt] = m_new;
-#pragma unroll
-            for (int db = 0; db < 4; db++)
-#pragma unroll
-                for (int i = 0; i < 16; i++) oacc[mt][db][i] *= alpha;
-        }
+    // Q and the mask row must have arrived before the loop: a wait the compiler can see here keeps it from
+    // placing a vmcnt(0) inside the loop, which would also drain the asynchronous tile loads every iteration
+    wait_vmcnt<0>();
 
-        // ---- O^T += V^T P^T
-        const int g16 = lane >> 4, i16 = lane & 15;
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-            for (int st = 0; st < 2; st++) {
-                const int keyb = 32 * kb + 16 * st + 4 * hh + (i16 >> 2);
-#pragma unroll
-                for (int db = 0; db < 4; db++) {
-                    const int col = (32 * db + 16 * (g16 & 1) + 4 * (i16 & 3)) * 2;
-                    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-                    const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (lds_s16x4 *)(lds_v + keyb * V_STRIDE + col));
-                    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (lds_s16x4 *)(lds_v + (keyb + 8) * V_STRIDE + col));
-                    const bf16x4 a0 = __builtin_bit_cast(bf16x4, v0), a1 = __builtin_bit_cast(bf16x4, v1);
-                    const bf16x8 a = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-                    for (int mt = 0; mt < MT; mt++)
-                        oacc[mt][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pfrag[kb][mt][st], oacc[mt][db], 0, 0, 0);
-                }
-            }
+    // per-lane LDS offsets (bytes within a tile) that do not depend on the tile
+    const int g16 = lane >> 4, i16 = lane & 15;
+    const int vrow = 4 * hh + (i16 >> 2);  // V row within a 16-key step (second read: +8)
+    TileView tv{nullptr, nullptr, c32 * ROW_BYTES, swz_of_row(c32), vrow, swz_of_row(vrow),
+                2 * (g16 & 1) + ((i16 & 3) >> 1), 8 * (i16 & 1), hh};
+
+    // ring step shared by both loops below: wait for tile ti, barrier, refill the stage tile ti-1 used
+    auto ring_step = [&](int ti) {
+        const int ahead = min(NS - 2, nt - 1 - ti);  // younger tiles whose loads may still be outstanding
+        if (NS >= 4 && ahead >= 2) wait_vmcnt<2 * LPW>();
+        else if (NS >= 3 && ahead == 1) wait_vmcnt<LPW>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();  // everyone's part of tile ti is in LDS; everyone is done with tile ti-1
+        asm volatile("" ::: "memory");
+        if (ti + NS - 1 < nt) issue(ti + NS - 1);
+        tv.lk = smem + (ti % NS) * STAGE_BYTES;
+        tv.lv = tv.lk + TILE_BYTES;
+    };
+
+    // full prefix tiles: no masking code at all
+    int ti = 0;
+    for (; ti < nfull; ti++) {
+        ring_step(ti);
+        process_tile<false>(tv, qreg, oacc, m_run, l_run, p.scale_log2, ~0ull);
+    }
+    // the ragged last prefix tile (keys >= k1 hidden) and the tree tiles (ancestor bitmask of the row)
+    for (; ti < nt; ti++) {
+        ring_step(ti);
+        uint64_t vis;
+        if (ti < npt) vis = (1ull << (k1 - k0 - nfull * KT)) - 1ull;  // 1..63 visible keys
+        else vis = (ti - npt) ? mbits1 : mbits0;
+        process_tile<true>(tv, qreg, oacc, m_run, l_run, p.scale_log2, vis);
     }
 
     // ---- epilogue
-    if (!active) return;
+    if (!active || kq >= p.T_max) return;
     uint16_t *out = static_cast<uint16_t *>(p.out);
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const size_t lrow = ((size_t)b * p.Hq + h) * p.T_max + kq;
+    if (direct) {
+        const size_t orow = (((size_t)b * p.T_max + kq) * p.Hq + h) * D;
+        const float inv = rv ? 1.f / l_tot : 0.f;
 #pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        const int kq = row0 + 32 * mt + c32;
-        if (kq >= p.T_max) continue;
-        const float l_tot = l_run[mt] + __shfl_xor(l_run[mt], 32);
-        const size_t lrow = ((size_t)b * p.Hq + h) * p.T_max + kq;
-        if (direct) {
-            const size_t orow = (((size_t)b * p.T_max + kq) * p.Hq + h) * D;
-            const bool rv = kq < n;
-            const float inv = rv ? 1.f / l_tot : 0.f;
+        for (int db = 0; db < 4; db++)
 #pragma unroll
-            for (int db = 0; db < 4; db++)
-#pragma unroll
-                for (int ig = 0; ig < 4; ig++) {
-                    const int dcol = 32 * db + 8 * ig + 4 * hh;
-                    uint2 w;
-                    w.x = rv ? pack_bf16x2(oacc[mt][db][4 * ig] * inv, oacc[mt][db][4 * ig + 1] * inv) : 0u;
-                    w.y = rv ? pack_bf16x2(oacc[mt][db][4 * ig + 2] * inv, oacc[mt][db][4 * ig + 3] * inv) : 0u;
-                    *reinterpret_cast<uint2 *>(out + orow + dcol) = w;
-                }
-            if (p.lse && hh == 0) p.lse[lrow] = rv ? (m_run[mt] + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-        } else if (kq < n) {
-            const size_t pr = lrow * p.nsplit + s;
-#pragma unroll
-            for (int db = 0; db < 4; db++)
-#pragma unroll
-                for (int ig = 0; ig < 4; ig++) {
-                    const int dcol = 32 * db + 8 * ig + 4 * hh;
-                    float4 w = {oacc[mt][db][4 * ig], oacc[mt][db][4 * ig + 1], oacc[mt][db][4 * ig + 2],
-                                oacc[mt][db][4 * ig + 3]};
-                    *reinterpret_cast<float4 *>(p.part_o + pr * D + dcol) = w;
-                }
-            if (hh == 0) {
-                p.part_m[pr] = m_run[mt];
-                p.part_l[pr] = l_tot;
+            for (int ig = 0; ig < 4; ig++) {
+                const int dcol = 32 * db + 8 * ig + 4 * hh;
+                uint2 w;
+                w.x = rv ? pack_bf16x2(oacc[db][4 * ig] * inv, oacc[db][4 * ig + 1] * inv) : 0u;
+                w.y = rv ? pack_bf16x2(oacc[db][4 * ig + 2] * inv, oacc[db][4 * ig + 3] * inv) : 0u;
+                *reinterpret_cast<uint2 *>(out + orow + dcol) = w;
             }
+        if (p.lse && hh == 0) p.lse[lrow] = rv ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+    } else if (rv) {
+        const size_t pr = part_row(p, b, s, h, kq);
+#pragma unroll
+        for (int db = 0; db < 4; db++)
+#pragma unroll
+            for (int ig = 0; ig < 4; ig++) {
+                const int dcol = 32 * db + 8 * ig + 4 * hh;
+                float4 w = {oacc[db][4 * ig], oacc[db][4 * ig + 1], oacc[db][4 * ig + 2], oacc[db][4 * ig + 3]};
+                *reinterpret_cast<float4 *>(p.part_o + pr * D + dcol) = w;
+            }
+        if (hh == 0) {
+            p.part_m[pr] = m_run;
+            p.part_l[pr] = l_tot;
         }
     }
 }
@@ -510,7 +669,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnParams p) {
 // ----------------------------------------------------------------------------------------------
 struct Plan {
     bool mfma;
-    int mt, pairs, wgp, chunk, nsplit;
+    int nw, pairs, wgp, chunk, nsplit;
 };
 
 static bool supported(const etv_attn_desc *h) {
@@ -524,10 +683,10 @@ static Plan make_plan(const etv_attn_desc *h) {
     pl.mfma = (h->dtype == ETV_BF16 && h->d == 128 && !(h->flags & ETV_ATTN_FLAG_GENERIC));
     long units;
     if (pl.mfma) {
-        pl.mt = h->T_max <= 32 ? 1 : 2;
-        const int nrc = (h->T_max + 32 * pl.mt - 1) / (32 * pl.mt);
-        pl.pairs = (h->Hq / h->Hkv) * nrc;
-        pl.wgp = (pl.pairs + 3) / 4;
+        const int nrc = (h->T_max + 31) / 32;        // 32-row chunks
+        pl.pairs = (h->Hq / h->Hkv) * nrc;           // (head in group, row chunk) pairs per KV head
+        pl.nw = pl.pairs > 4 ? 8 : 4;                // wavefronts per workgroup
+        pl.wgp = (pl.pairs + pl.nw - 1) / pl.nw;
         units = (long)max(1, h->B) * h->Hkv * pl.wgp;
     } else {
         units = ((long)max(1, h->B) * h->Hq * h->T_max + 7) / 8;  // 8 resident wavefronts ~ one workgroup slot
@@ -536,7 +695,7 @@ static Plan make_plan(const etv_attn_desc *h) {
     if (h->kv_split > 0) {
         tiles_per_split = (h->kv_split + KT - 1) / KT;
     } else {
-        const long target = 512;  // workgroups wanted in flight: two per compute unit
+        const long target = (pl.mfma && pl.nw == 4) ? 512 : 256;  // workgroups that fit on the chip at once
         long want = (target + units - 1) / units;
         if (want < 1) want = 1;
         if (want > tiles) want = tiles;
@@ -545,6 +704,18 @@ static Plan make_plan(const etv_attn_desc *h) {
     pl.chunk = tiles_per_split * KT;
     pl.nsplit = (tiles + tiles_per_split - 1) / tiles_per_split;
     return pl;
+}
+
+template <int NW, int NS, bool PAGED>
+static int32_t launch_mfma(const AttnParams &p, dim3 grid, hipStream_t st) {
+    constexpr size_t lds = (size_t)NS * STAGE_BYTES;
+    static const bool lds_ok = [] {  // opt in to more than 64 KiB of dynamic LDS, once per process
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<NW, NS, PAGED>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
+    }();
+    if (!lds_ok) return ETV_ERR_HIP;
+    hipLaunchKernelGGL((attn_mfma_kernel<NW, NS, PAGED>), grid, dim3(NW * 64), lds, st, p);
+    return check_launch();
 }
 
 }  // namespace etv
@@ -605,12 +776,14 @@ extern "C" int32_t etv_tree_verify_attention(const etv_attn_desc *h, const void 
         p.part_l = p.part_m + rows;
     }
     hipStream_t st = as_stream(stream);
+    int32_t rc;
     if (pl.mfma) {
         dim3 grid(pl.nsplit, h->Hkv * pl.wgp, h->B);
-        if (pl.mt == 1)
-            hipLaunchKernelGGL(attn_mfma_kernel<1>, grid, dim3(256), 0, st, p);
-        else
-            hipLaunchKernelGGL(attn_mfma_kernel<2>, grid, dim3(256), 0, st, p);
+        const bool paged = h->block_size > 0;
+        // 8 wavefronts: one workgroup per compute unit with a 4-stage ring (128 KiB of LDS);
+        // 4 wavefronts: two workgroups per compute unit with 2 stages each
+        if (pl.nw == 8) rc = paged ? launch_mfma<8, 4, true>(p, grid, st) : launch_mfma<8, 4, false>(p, grid, st);
+        else rc = paged ? launch_mfma<4, 2, true>(p, grid, st) : launch_mfma<4, 2, false>(p, grid, st);
     } else {
         dim3 grid(h->T_max, h->Hq, h->B * pl.nsplit);
         if (h->dtype == ETV_F32 && h->d == 64)
@@ -621,8 +794,8 @@ extern "C" int32_t etv_tree_verify_attention(const etv_attn_desc *h, const void 
             hipLaunchKernelGGL((attn_generic_kernel<uint16_t, 64>), grid, dim3(64), 0, st, p);
         else
             hipLaunchKernelGGL((attn_generic_kernel<uint16_t, 128>), grid, dim3(64), 0, st, p);
+        rc = check_launch();
     }
-    int32_t rc = check_launch();
     if (rc != ETV_OK || pl.nsplit == 1) return rc;
     dim3 cgrid(h->T_max, h->Hq, h->B);
     if (h->dtype == ETV_F32 && h->d == 64)
