@@ -261,9 +261,15 @@ __global__ void __launch_bounds__(D) attn_combine_kernel(AttnParams p) {
 // (global_load_lds_dwordx4: no registers, completion tracked by vmcnt) into a ring of NS stages, so
 // NS-1 tiles (32 KiB each) are in flight per workgroup while one is being consumed; one workgroup
 // barrier per tile.  A direct-to-LDS load writes lane i's 16 bytes at (base + 16 i), so rows cannot be
-// padded; instead the 16-byte chunk c of key row r is stored at chunk position c ^ f(r) with
-// f(r) = ((r & 3) << 1) | ((r >> 2) & 1), which spreads both the 16-byte K reads (8 consecutive rows, same
-// chunk) and the 8-byte transpose reads of V (4 consecutive rows x 32 B) over all LDS banks.
+// padded; instead the 16-byte chunk c of key row r is stored at chunk position c ^ (r & 15) in the K tile
+// and c ^ (((r & 3) << 1) | ((r >> 2) & 1)) in the V tile, which spreads the 16-byte K reads (consecutive rows,
+// same chunk) and the 8-byte transpose reads of V (4 consecutive rows x 32 B) over the LDS banks.
+//
+// The two wavefronts of a SIMD (w and w+4) run one phase apart: wavefronts 0..3 do QK(t), softmax(t),
+// PV(t) inside ring step t, wavefronts 4..7 do PV(t-1), QK(t), softmax(t).  The tile barrier would otherwise
+// keep them in lockstep, both wanting the matrix core, then both the vector ALU; shifted, one wavefront's
+// softmax overlaps the other's products.  A V tile therefore lives one ring step longer than a K tile, and
+// the ring refills the stage of tile t-2 (two tiles in flight) rather than that of tile t-1.
 //
 // Per 64-key tile and wavefront (32x32x16 MFMA, 64-lane layouts: A/B operand lane = (row|col l%32,
 // 8 contraction values at 8*(l/32)); accumulator lane = (col l%32, rows 8*(i/4) + 4*(l/32) + i%4)):
@@ -303,51 +309,63 @@ template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
-__device__ __forceinline__ int swz_of_row(int r) { return ((r & 3) << 1) | ((r >> 2) & 1); }
+// chunk-position swizzles (measured on gfx950: 16-byte reads reach the full 256 B/clk only with a 4-bit
+// row term; the 8-byte transpose reads are fastest with the 3-bit term below)
+__device__ __forceinline__ int kswz_of_row(int r) { return r & 15; }
+__device__ __forceinline__ int vswz_of_row(int r) { return ((r & 3) << 1) | ((r >> 2) & 1); }
 
 extern __shared__ __attribute__((aligned(1024))) uint8_t attn_smem[];
 
 // Asynchronous loads of one 64-key K/V tile into ring stage (ti % NS).  A tile is 16 chunk pairs of
-// 1 KiB (4 key rows of K, the same 4 rows of V).  Wavefront w issues pairs w, w+NW, ...; in a chunk lane i
+// 1 KiB (4 key rows of K, the same 4 rows of V).  Issuing wavefront w takes pairs w, w+4, ...; in a chunk lane i
 // fetches key row 4j + i/16 and the 16-byte piece that belongs at chunk position i%16 of that row.
 template <int NW>
 struct TileLoader {
-    static constexpr int U = 16 / NW;  // chunk pairs per wavefront and tile
+    // wavefronts that issue loads: all 4 of a small workgroup; of 8, only wavefronts 0..3, which otherwise
+    // idle at the tile barrier while wavefronts 4..7 (one phase behind) finish their longer chain
+    static constexpr int NI = 4;
+    static constexpr int U = 16 / NI;  // chunk pairs per issuing wavefront and tile
     const uint8_t *kc, *vc, *kt, *vt;
     const int32_t *bt;
     size_t row_stride, seq_off, blk_stride, head_off;
     uint32_t smem_addr;
     int wave, l_row, l_pos, k0, k1, npt, n;
-    size_t lane_off_contig[U];   // per-lane part of the source offset, contiguous cache
-    uint32_t lane_off_paged[U];  // same, paged cache (within one block of one head)
+    size_t lane_row_contig[U];   // per-lane row part of the source offset, contiguous cache
+    uint32_t lane_row_paged[U];  // same, paged cache (row within one block of one head)
+    uint32_t kcol[U], vcol[U];   // per-lane source column (bytes) for the K tile / the V tile swizzle
 };
 
-// full prefix tile (all 64 keys exist): straight-line address arithmetic
+// full prefix tile (all 64 keys exist): straight-line address arithmetic.  For a paged cache the physical
+// block ids are fetched with scalar loads by fetch_blocks() ahead of the wait and barrier of the ring step,
+// so their latency is hidden; the block table is read-only for the kernel (constant address space).
+template <int NW>
+__device__ __forceinline__ void fetch_blocks(const TileLoader<NW> &ld, int ti, int (&blk)[TileLoader<NW>::U]) {
+    const int lb0 = (ld.k0 + ti * KT) >> 4;
+#pragma unroll
+    for (int u = 0; u < TileLoader<NW>::U; u++)
+        blk[u] = ((const_i32_ptr)(uintptr_t)ld.bt)[lb0 + ((ld.wave + TileLoader<NW>::NI * u) >> 2)];
+}
+
 template <int NW, int NS, bool PAGED>
-__device__ __forceinline__ void issue_full_tile(const TileLoader<NW> &ld, int ti) {
-    constexpr int U = TileLoader<NW>::U;
-    const int base = ld.k0 + ti * KT;
+__device__ __forceinline__ void issue_full_tile(const TileLoader<NW> &ld, int ti, const int (&blk)[TileLoader<NW>::U]) {
+    constexpr int U = TileLoader<NW>::U, NI = TileLoader<NW>::NI;
     const uint32_t stage = ld.smem_addr + (uint32_t)(ti % NS) * STAGE_BYTES;
     if (PAGED) {
-        int blk[U];
-#pragma unroll
-        for (int u = 0; u < U; u++)  // scalar loads: the block table is read-only for the kernel
-            blk[u] = ((const_i32_ptr)(uintptr_t)ld.bt)[(base >> 4) + ((ld.wave + NW * u) >> 2)];
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            const int j = ld.wave + NW * u;
-            const size_t off = (size_t)blk[u] * ld.blk_stride + ld.head_off + ld.lane_off_paged[u];
-            async_load16(ld.kc + off, stage + j * 1024);
-            async_load16(ld.vc + off, stage + TILE_BYTES + j * 1024);
+            const int j = ld.wave + NI * u;
+            const size_t off = (size_t)blk[u] * ld.blk_stride + ld.head_off + ld.lane_row_paged[u];
+            async_load16(ld.kc + off + ld.kcol[u], stage + j * 1024);
+            async_load16(ld.vc + off + ld.vcol[u], stage + TILE_BYTES + j * 1024);
         }
     } else {
-        const size_t tile_off = ld.seq_off + (size_t)base * ld.row_stride;
+        const size_t tile_off = ld.seq_off + (size_t)(ld.k0 + ti * KT) * ld.row_stride;
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            const int j = ld.wave + NW * u;
-            const size_t off = tile_off + ld.lane_off_contig[u];
-            async_load16(ld.kc + off, stage + j * 1024);
-            async_load16(ld.vc + off, stage + TILE_BYTES + j * 1024);
+            const int j = ld.wave + NI * u;
+            const size_t off = tile_off + ld.lane_row_contig[u];
+            async_load16(ld.kc + off + ld.kcol[u], stage + j * 1024);
+            async_load16(ld.vc + off + ld.vcol[u], stage + TILE_BYTES + j * 1024);
         }
     }
 }
@@ -355,7 +373,7 @@ __device__ __forceinline__ void issue_full_tile(const TileLoader<NW> &ld, int ti
 // ragged last prefix tile or tree tile: rows past the end re-read the last valid row (masked later)
 template <int NW, int NS>
 __device__ __forceinline__ void issue_edge_tile(const TileLoader<NW> &ld, int ti) {
-    constexpr int U = TileLoader<NW>::U;
+    constexpr int U = TileLoader<NW>::U, NI = TileLoader<NW>::NI;
     const bool tree = ti >= ld.npt;
     const int base = tree ? (ti - ld.npt) * KT : ld.k0 + ti * KT;
     const int last = (tree ? ld.n : ld.k1) - 1;
@@ -364,7 +382,7 @@ __device__ __forceinline__ void issue_edge_tile(const TileLoader<NW> &ld, int ti
     const uint8_t *vsrc = tree ? ld.vt : ld.vc;
 #pragma unroll
     for (int u = 0; u < U; u++) {
-        const int j = ld.wave + NW * u;
+        const int j = ld.wave + NI * u;
         const int r_in = 4 * j + ld.l_row;
         const int key = min(base + r_in, last);
         size_t off;
@@ -378,15 +396,13 @@ __device__ __forceinline__ void issue_edge_tile(const TileLoader<NW> &ld, int ti
         } else {
             off = ld.seq_off + (size_t)key * ld.row_stride;
         }
-        off += (ld.l_pos ^ swz_of_row(r_in)) * 16;
-        async_load16(ksrc + off, stage + j * 1024);
-        async_load16(vsrc + off, stage + TILE_BYTES + j * 1024);
+        async_load16(ksrc + off + ld.kcol[u], stage + j * 1024);
+        async_load16(vsrc + off + ld.vcol[u], stage + TILE_BYTES + j * 1024);
     }
 }
 
 // LDS view of one staged tile plus the per-lane fragment offsets (bytes) that do not depend on the tile.
 struct TileView {
-    const uint8_t *lk, *lv;
     int krow;          // K fragment row offset: row (lane%32) of key block 0; block 1 is 32 rows further
     int ksw;           // swizzle term of that row (the same for row + 32)
     int vrow, vsw, vchunk, vsub;  // V transpose-read row within a 16-key step, its swizzle, chunk, sub-offset
@@ -399,12 +415,30 @@ struct TileView {
 // touch) becomes rare after the first tiles.
 constexpr float kLazy = 8.0f;
 
-// One 64-key tile for one wavefront (32 query rows).  MASKED: key kin of the tile is visible to the
-// lane's row iff bit kin of `vis`.
+// V^T fragments of 32 keys (key block kb) of the V tile at lv.
+__device__ __forceinline__ void load_v_frags(const TileView &tv, const uint8_t *lv, int kb, bf16x8 (&vf)[2][4]) {
+#pragma unroll
+    for (int st = 0; st < 2; st++) {
+        const uint8_t *vr = lv + (32 * kb + 16 * st + tv.vrow) * ROW_BYTES + tv.vsub;
+#pragma unroll
+        for (int db = 0; db < 4; db++) {
+            const int cpos = ((4 * db + tv.vchunk) ^ tv.vsw) << 4;
+            const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vr + cpos));
+            const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vr + 8 * ROW_BYTES + cpos));
+            const bf16x4 a0 = __builtin_bit_cast(bf16x4, v0), a1 = __builtin_bit_cast(bf16x4, v1);
+            vf[st][db] = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    }
+}
+
+// First half of a 64-key tile for one wavefront (32 query rows): S^T = K Q^T, mask, running reference,
+// P^T = exp2(S^T * scale - m) packed to bf16 in pf[key block][16-key step].  MASKED: key kin of the tile is
+// visible to the lane's row iff bit kin of `vis`.
 template <bool MASKED>
-__device__ __forceinline__ void process_tile(const TileView &tv, const bf16x8 (&qreg)[8], f32x16 (&oacc)[4],
-                                             float &m_run, float &l_run, float scale_log2, uint64_t vis) {
-    // ---- S^T = K Q^T: two independent accumulator chains (keys 0..31 and 32..63)
+__device__ __forceinline__ void qk_softmax(const TileView &tv, const uint8_t *lk, const bf16x8 (&qreg)[8],
+                                           f32x16 (&oacc)[4], float &m_run, float &l_run, float scale_log2,
+                                           uint64_t vis, bf16x8 (&pf)[2][2]) {
+    // two independent accumulator chains (keys 0..31 and 32..63)
     f32x16 s0, s1;
 #pragma unroll
     for (int i = 0; i < 16; i++) { s0[i] = 0.f; s1[i] = 0.f; }
@@ -413,8 +447,8 @@ __device__ __forceinline__ void process_tile(const TileView &tv, const bf16x8 (&
 #pragma unroll
         for (int kk = 0; kk < 8; kk++) {
             const int col = (((2 * kk + tv.hh) ^ tv.ksw) << 4);
-            ka[kk] = *reinterpret_cast<const bf16x8 *>(tv.lk + tv.krow + col);
-            kb[kk] = *reinterpret_cast<const bf16x8 *>(tv.lk + tv.krow + 32 * ROW_BYTES + col);
+            ka[kk] = *reinterpret_cast<const bf16x8 *>(lk + tv.krow + col);
+            kb[kk] = *reinterpret_cast<const bf16x8 *>(lk + tv.krow + 32 * ROW_BYTES + col);
         }
 #pragma unroll
         for (int kk = 0; kk < 8; kk++) {
@@ -422,25 +456,6 @@ __device__ __forceinline__ void process_tile(const TileView &tv, const bf16x8 (&
             s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[kk], qreg[kk], s1, 0, 0, 0);
         }
     }
-    // V^T fragments of the first 32 keys fly while the softmax runs
-    bf16x8 vf[2][4];
-    auto load_v = [&](int kb) {
-#pragma unroll
-        for (int st = 0; st < 2; st++) {
-            const uint8_t *vr = tv.lv + (32 * kb + 16 * st + tv.vrow) * ROW_BYTES + tv.vsub;
-#pragma unroll
-            for (int db = 0; db < 4; db++) {
-                const int cpos = ((4 * db + tv.vchunk) ^ tv.vsw) << 4;
-                const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vr + cpos));
-                const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vr + 8 * ROW_BYTES + cpos));
-                const bf16x4 a0 = __builtin_bit_cast(bf16x4, v0), a1 = __builtin_bit_cast(bf16x4, v1);
-                vf[st][db] = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-        }
-    };
-    load_v(0);
-
-    // ---- mask, running reference, P^T = exp2(S^T * scale - m) packed to bf16
     if (MASKED) {
         const uint32_t lo = (uint32_t)(vis >> (4 * tv.hh)), hi = (uint32_t)(vis >> (32 + 4 * tv.hh));
 #pragma unroll
@@ -469,28 +484,30 @@ __device__ __forceinline__ void process_tile(const TileView &tv, const bf16x8 (&
             for (int i = 0; i < 16; i++) oacc[db][i] *= alpha;
     }
     const float neg_m = (MASKED && m_run == -INFINITY) ? 0.f : -m_run;
-    bf16x8 pf[2][2];
     float psum = 0.f;
-    {
-        uint32_t pk0[8], pk1[8];
+    uint32_t pk0[8], pk1[8];
 #pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-            const float a0 = __builtin_amdgcn_exp2f(fmaf(s0[i], scale_log2, neg_m));
-            const float a1 = __builtin_amdgcn_exp2f(fmaf(s0[i + 1], scale_log2, neg_m));
-            const float b0 = __builtin_amdgcn_exp2f(fmaf(s1[i], scale_log2, neg_m));
-            const float b1 = __builtin_amdgcn_exp2f(fmaf(s1[i + 1], scale_log2, neg_m));
-            psum += (a0 + a1) + (b0 + b1);
-            pk0[i >> 1] = pack_bf16x2(a0, a1);
-            pk1[i >> 1] = pack_bf16x2(b0, b1);
-        }
-        const uint4 l0 = {pk0[0], pk0[1], pk0[2], pk0[3]}, h0 = {pk0[4], pk0[5], pk0[6], pk0[7]};
-        const uint4 l1 = {pk1[0], pk1[1], pk1[2], pk1[3]}, h1 = {pk1[4], pk1[5], pk1[6], pk1[7]};
-        pf[0][0] = __builtin_bit_cast(bf16x8, l0); pf[0][1] = __builtin_bit_cast(bf16x8, h0);
-        pf[1][0] = __builtin_bit_cast(bf16x8, l1); pf[1][1] = __builtin_bit_cast(bf16x8, h1);
+    for (int i = 0; i < 16; i += 2) {
+        const float a0 = __builtin_amdgcn_exp2f(fmaf(s0[i], scale_log2, neg_m));
+        const float a1 = __builtin_amdgcn_exp2f(fmaf(s0[i + 1], scale_log2, neg_m));
+        const float b0 = __builtin_amdgcn_exp2f(fmaf(s1[i], scale_log2, neg_m));
+        const float b1 = __builtin_amdgcn_exp2f(fmaf(s1[i + 1], scale_log2, neg_m));
+        psum += (a0 + a1) + (b0 + b1);
+        pk0[i >> 1] = pack_bf16x2(a0, a1);
+        pk1[i >> 1] = pack_bf16x2(b0, b1);
     }
+    const uint4 l0 = {pk0[0], pk0[1], pk0[2], pk0[3]}, h0 = {pk0[4], pk0[5], pk0[6], pk0[7]};
+    const uint4 l1 = {pk1[0], pk1[1], pk1[2], pk1[3]}, h1 = {pk1[4], pk1[5], pk1[6], pk1[7]};
+    pf[0][0] = __builtin_bit_cast(bf16x8, l0); pf[0][1] = __builtin_bit_cast(bf16x8, h0);
+    pf[1][0] = __builtin_bit_cast(bf16x8, l1); pf[1][1] = __builtin_bit_cast(bf16x8, h1);
     l_run += psum;
+}
 
-    // ---- O^T += V^T P^T: four independent accumulator chains (d blocks)
+// Second half: O^T += V^T P^T over the 64 keys of the V tile at lv; four independent accumulator chains.
+// The first 32 keys' fragments may have been read ahead (vf0_ready).
+__device__ __forceinline__ void pv_accumulate(const TileView &tv, const uint8_t *lv, const bf16x8 (&pf)[2][2],
+                                              f32x16 (&oacc)[4], bf16x8 (&vf)[2][4], bool vf0_ready) {
+    if (!vf0_ready) load_v_frags(tv, lv, 0, vf);
 #pragma unroll
     for (int kb = 0; kb < 2; kb++) {
         bf16x8 va[2][4];
@@ -498,7 +515,7 @@ __device__ __forceinline__ void process_tile(const TileView &tv, const bf16x8 (&
         for (int st = 0; st < 2; st++)
 #pragma unroll
             for (int db = 0; db < 4; db++) va[st][db] = vf[st][db];
-        if (kb == 0) load_v(1);  // the second half's fragments fly during the first half's products
+        if (kb == 0) load_v_frags(tv, lv, 1, vf);  // the second half's fragments fly during the first half's products
 #pragma unroll
         for (int st = 0; st < 2; st++)
 #pragma unroll
@@ -510,7 +527,7 @@ __device__ __forceinline__ void process_tile(const TileView &tv, const bf16x8 (&
 template <int NW, int NS, bool PAGED>
 __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     constexpr int D = 128;
-    constexpr int LPW = 2 * TileLoader<NW>::U;  // direct-to-LDS loads each wavefront issues per tile
+    constexpr int LPW = 2 * TileLoader<NW>::U;  // direct-to-LDS loads an issuing wavefront issues per tile
     uint8_t *const smem = attn_smem;
     const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)attn_smem;
 
@@ -553,18 +570,26 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     ld.k0 = k0; ld.k1 = k1; ld.npt = npt; ld.n = n;
 #pragma unroll
     for (int u = 0; u < TileLoader<NW>::U; u++) {
-        const int r_in = 4 * (wave + NW * u) + ld.l_row;
-        const int col = (ld.l_pos ^ swz_of_row(r_in)) * 16;
-        ld.lane_off_contig[u] = (size_t)r_in * ld.row_stride + col;
-        ld.lane_off_paged[u] = (uint32_t)((r_in & 15) * ROW_BYTES + col);
+        const int r_in = 4 * (wave + TileLoader<NW>::NI * u) + ld.l_row;
+        ld.kcol[u] = (uint32_t)((ld.l_pos ^ kswz_of_row(r_in)) * 16);
+        ld.vcol[u] = (uint32_t)((ld.l_pos ^ vswz_of_row(r_in)) * 16);
+        ld.lane_row_contig[u] = (size_t)r_in * ld.row_stride;
+        ld.lane_row_paged[u] = (uint32_t)((r_in & 15) * ROW_BYTES);
     }
+    const bool issuer = wave < TileLoader<NW>::NI;
     auto issue = [&](int ti) {
-        if (ti < nfull) issue_full_tile<NW, NS, PAGED>(ld, ti);
-        else issue_edge_tile<NW, NS>(ld, ti);
+        if (!issuer) return;
+        if (ti < nfull) {
+            int blk[TileLoader<NW>::U];
+            if (PAGED) fetch_blocks<NW>(ld, ti, blk);
+            issue_full_tile<NW, NS, PAGED>(ld, ti, blk);
+        } else {
+            issue_edge_tile<NW, NS>(ld, ti);
+        }
     };
 
     // prologue: fill NS-1 stages, then fetch Q and the mask row while those loads fly
-    for (int ti = 0; ti < NS - 1 && ti < nt; ti++) issue(ti);
+    for (int ti = 0; ti < ((NW == 8) ? NS - 2 : NS - 1) && ti < nt; ti++) issue(ti);
 
     const uint16_t *qp = static_cast<const uint16_t *>(p.q);
     // Q as B operand: lane holds query row kq, d values 16*kk + 8*hh .. +7
@@ -597,35 +622,62 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     // per-lane LDS offsets (bytes within a tile) that do not depend on the tile
     const int g16 = lane >> 4, i16 = lane & 15;
     const int vrow = 4 * hh + (i16 >> 2);  // V row within a 16-key step (second read: +8)
-    TileView tv{nullptr, nullptr, c32 * ROW_BYTES, swz_of_row(c32), vrow, swz_of_row(vrow),
+    TileView tv{c32 * ROW_BYTES, kswz_of_row(c32), vrow, vswz_of_row(vrow),
                 2 * (g16 & 1) + ((i16 & 3) >> 1), 8 * (i16 & 1), hh};
 
-    // ring step shared by both loops below: wait for tile ti, barrier, refill the stage tile ti-1 used
+    // Ring step: wait for tile ti, barrier, refill.  PD = tiles in flight behind the one being consumed.
+    // With 8 wavefronts the V tile of step ti-1 is still being read by wavefronts 4..7 during step ti, so
+    // the stage that is refilled is the one of tile ti-2.
+    constexpr bool kShifted = (NW == 8);
+    constexpr int PD = kShifted ? NS - 2 : NS - 1;
+    static_assert(PD >= 1 && PD <= 3, "ring depth");
     auto ring_step = [&](int ti) {
-        const int ahead = min(NS - 2, nt - 1 - ti);  // younger tiles whose loads may still be outstanding
-        if (NS >= 4 && ahead >= 2) wait_vmcnt<2 * LPW>();
-        else if (NS >= 3 && ahead == 1) wait_vmcnt<LPW>();
+        const int tn = ti + PD;  // tile to issue in this step
+        int blk[TileLoader<NW>::U];
+        const bool full_next = issuer && tn < nfull;
+        if (PAGED && full_next) fetch_blocks<NW>(ld, tn, blk);  // scalar loads fly during the wait below
+        const int ahead = min(PD - 1, nt - 1 - ti);  // younger tiles whose loads may still be outstanding
+        if (PD >= 3 && ahead >= 2) wait_vmcnt<2 * LPW>();
+        else if (PD >= 2 && ahead == 1) wait_vmcnt<LPW>();
         else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();  // everyone's part of tile ti is in LDS; everyone is done with tile ti-1
+        __builtin_amdgcn_s_barrier();  // everyone's part of tile ti is in LDS; the refilled stage is no longer read
         asm volatile("" ::: "memory");
-        if (ti + NS - 1 < nt) issue(ti + NS - 1);
-        tv.lk = smem + (ti % NS) * STAGE_BYTES;
-        tv.lv = tv.lk + TILE_BYTES;
+        if (full_next) issue_full_tile<NW, NS, PAGED>(ld, tn, blk);
+        else if (issuer && tn < nt) issue_edge_tile<NW, NS>(ld, tn);
     };
-
-    // full prefix tiles: no masking code at all
+    auto tile_vis = [&](int ti) -> uint64_t {
+        if (ti < npt) return (1ull << (k1 - k0 - nfull * KT)) - 1ull;  // ragged last prefix tile: 1..63 keys
+        return (ti - npt) ? mbits1 : mbits0;                            // tree tile: the row's ancestor bits
+    };
+    bf16x8 pf[2][2], vf[2][4];
     int ti = 0;
-    for (; ti < nfull; ti++) {
-        ring_step(ti);
-        process_tile<false>(tv, qreg, oacc, m_run, l_run, p.scale_log2, ~0ull);
-    }
-    // the ragged last prefix tile (keys >= k1 hidden) and the tree tiles (ancestor bitmask of the row)
-    for (; ti < nt; ti++) {
-        ring_step(ti);
-        uint64_t vis;
-        if (ti < npt) vis = (1ull << (k1 - k0 - nfull * KT)) - 1ull;  // 1..63 visible keys
-        else vis = (ti - npt) ? mbits1 : mbits0;
-        process_tile<true>(tv, qreg, oacc, m_run, l_run, p.scale_log2, vis);
+    if (!kShifted || wave < 4) {
+        // QK(t), softmax(t), PV(t) within ring step t
+        for (; ti < nfull; ti++) {  // full prefix tiles: no masking code at all
+            ring_step(ti);
+            const uint8_t *lk = smem + (ti % NS) * STAGE_BYTES;
+            qk_softmax<false>(tv, lk, qreg, oacc, m_run, l_run, p.scale_log2, ~0ull, pf);
+            pv_accumulate(tv, lk + TILE_BYTES, pf, oacc, vf, false);
+        }
+        for (; ti < nt; ti++) {     // ragged last prefix tile and tree tiles
+            ring_step(ti);
+            const uint8_t *lk = smem + (ti % NS) * STAGE_BYTES;
+            qk_softmax<true>(tv, lk, qreg, oacc, m_run, l_run, p.scale_log2, tile_vis(ti), pf);
+            pv_accumulate(tv, lk + TILE_BYTES, pf, oacc, vf, false);
+        }
+    } else {
+        // one phase behind: PV(t-1), QK(t), softmax(t) within ring step t; the last PV after the loop
+        for (; ti < nfull; ti++) {
+            ring_step(ti);
+            if (ti > 0) pv_accumulate(tv, smem + ((ti - 1) % NS) * STAGE_BYTES + TILE_BYTES, pf, oacc, vf, false);
+            qk_softmax<false>(tv, smem + (ti % NS) * STAGE_BYTES, qreg, oacc, m_run, l_run, p.scale_log2, ~0ull, pf);
+        }
+        for (; ti < nt; ti++) {
+            ring_step(ti);
+            if (ti > 0) pv_accumulate(tv, smem + ((ti - 1) % NS) * STAGE_BYTES + TILE_BYTES, pf, oacc, vf, false);
+            qk_softmax<true>(tv, smem + (ti % NS) * STAGE_BYTES, qreg, oacc, m_run, l_run, p.scale_log2, tile_vis(ti), pf);
+        }
+        if (nt > 0) pv_accumulate(tv, smem + ((nt - 1) % NS) * STAGE_BYTES + TILE_BYTES, pf, oacc, vf, false);
     }
 
     // ---- epilogue
@@ -695,11 +747,23 @@ static Plan make_plan(const etv_attn_desc *h) {
     if (h->kv_split > 0) {
         tiles_per_split = (h->kv_split + KT - 1) / KT;
     } else {
-        const long target = (pl.mfma && pl.nw == 4) ? 512 : 256;  // workgroups that fit on the chip at once
-        long want = (target + units - 1) / units;
-        if (want < 1) want = 1;
-        if (want > tiles) want = tiles;
-        tiles_per_split = (int)((tiles + want - 1) / want);
+        // Pick the split count with a small cost model (microseconds, fitted on MI355X): workgroups run in
+        // rounds of 256 (one per compute unit; the small-tree kernel fits two), each round costs its tiles
+        // plus a tree tile and ramp-up; every extra split writes and re-reads one (m, l, O) set per query row.
+        const double t_tile = pl.mfma ? 2.8 : 6.0;
+        const double slots = (pl.mfma && pl.nw == 4) ? 512.0 : 256.0;
+        const double part_us = 2.0 * max(1, h->B) * h->Hq * h->T_max * (h->d + 2.0) * 4.0 / 3.0e6;
+        double best = 1e30;
+        int best_n = 1;
+        for (int ns = 1; ns <= tiles; ns++) {
+            const int tps = (tiles + ns - 1) / ns;
+            const int n_eff = (tiles + tps - 1) / tps;
+            if (n_eff != ns) continue;
+            const double rounds = ceil((double)units * ns / slots);
+            const double est = rounds * (tps + 1.5) * t_tile + (ns > 1 ? 4.0 + ns * part_us : 0.0);
+            if (est < best) { best = est; best_n = ns; }
+        }
+        tiles_per_split = (tiles + best_n - 1) / best_n;
     }
     pl.chunk = tiles_per_split * KT;
     pl.nsplit = (tiles + tiles_per_split - 1) / tiles_per_split;
