@@ -309,6 +309,24 @@ template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
+// max / sum of a value with its partner in the other half of the wavefront (lane ^ 32) without touching
+// LDS: v_permlane32_swap exchanges the upper 32 lanes of one register with the lower 32 of another.  (A
+// ds_bpermute shuffle here would make the wavefront wait for its pending V-fragment LDS reads as well.)
+__device__ __forceinline__ float half_swap_max(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+// three-input max as one instruction.  (fmaxf would first canonicalise each MFMA result with an extra v_max,
+// doubling the instruction count of the row-max reduction; scores are never NaN here.)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float half_swap_sum(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 // chunk-position swizzles (measured on gfx950: 16-byte reads reach the full 256 B/clk only with a 4-bit
 // row term; the 8-byte transpose reads are fastest with the 3-bit term below)
 __device__ __forceinline__ int kswz_of_row(int r) { return r & 15; }
@@ -465,10 +483,14 @@ __device__ __forceinline__ void qk_softmax(const TileView &tv, const uint8_t *lk
             s1[i] = ((hi >> bit) & 1u) ? s1[i] : -INFINITY;
         }
     }
-    float rmax = fmaxf(s0[0], s1[0]);
+    float rmax = max3(s0[0], s1[0], s0[1]);
+    rmax = max3(rmax, s1[1], s0[2]);
+    rmax = max3(rmax, s1[2], s0[3]);
+    rmax = max3(rmax, s1[3], s1[15]);
 #pragma unroll
-    for (int i = 1; i < 16; i++) rmax = fmaxf(rmax, fmaxf(s0[i], s1[i]));
-    rmax = fmaxf(rmax, __shfl_xor(rmax, 32));
+    for (int i = 4; i < 15; i += 1) rmax = max3(rmax, s0[i], s1[i]);
+    rmax = fmaxf(rmax, s0[15]);
+    rmax = half_swap_max(rmax);
     const float tmax = rmax * scale_log2;  // scale_log2 > 0
     const bool lift = tmax > m_run + kLazy;  // also true for the first visible keys (reference -inf)
     if (__any(lift)) {
@@ -683,7 +705,7 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     // ---- epilogue
     if (!active || kq >= p.T_max) return;
     uint16_t *out = static_cast<uint16_t *>(p.out);
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float l_tot = half_swap_sum(l_run);
     const size_t lrow = ((size_t)b * p.Hq + h) * p.T_max + kq;
     if (direct) {
         const size_t orow = (((size_t)b * p.T_max + kq) * p.Hq + h) * D;
