@@ -37,6 +37,7 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--kv-split", type=int, default=0)
+    ap.add_argument("--attn-flags", type=int, default=0)
     ap.add_argument("--sets", type=int, default=0, help="cache sets to rotate over (0 = enough to exceed 640 MB)")
     return ap.parse_args()
 
@@ -61,7 +62,7 @@ def make_host_workload(name):
 class Step:
     """Device state of one workload and the launch sequence of a step."""
 
-    def __init__(self, wl, layers, nsets, kv_split):
+    def __init__(self, wl, layers, nsets, kv_split, attn_flags=0):
         import numpy as np
         import torch
         from paper_2603_08088_amd import api
@@ -102,7 +103,7 @@ class Step:
                              dense=torch.empty((B, 1, T, T), dtype=torch.uint8, device=dev),
                              depth=torch.empty((B, T), **i32), status=torch.empty((B,), **i32))
         self.out = torch.empty((layers, B, T, Hq, d), dtype=bf, device=dev)
-        self.desc = api.attn_desc(self.q[0], self.kt[0], self.kc[0][0], self.block_table, self.P_max, 0.0, kv_split)
+        self.desc = api.attn_desc(self.q[0], self.kt[0], self.kc[0][0], self.block_table, self.P_max, 0.0, kv_split, attn_flags)
         self.ws = torch.empty((max(256, api.tree_verify_attention_workspace_bytes(self.desc)),), dtype=torch.uint8,
                               device=dev)
         self.tokens3 = self.tokens.reshape(B, T, 1)
@@ -202,7 +203,7 @@ def main():
     api.lib()   # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     wl, desc_text = make_host_workload(a.workload)
-    st = Step(wl, a.layers, a.sets, a.kv_split)
+    st = Step(wl, a.layers, a.sets, a.kv_split, a.attn_flags)
     tokens_per_step = int(wl.n_nodes.sum())
 
     if a.no_graph:

@@ -127,6 +127,7 @@ typedef struct etv_attn_desc {
 } etv_attn_desc;
 
 #define ETV_ATTN_FLAG_GENERIC 1 /* run the fp32-VALU kernel even where the MFMA kernel applies (diagnostics) */
+#define ETV_ATTN_FLAG_SMALL_WG 2 /* always use 4-wavefront workgroups (tuning) */
 
 ETV_API size_t etv_tree_verify_attention_workspace_bytes(const etv_attn_desc *h_desc);
 

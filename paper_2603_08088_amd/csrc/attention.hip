@@ -554,7 +554,10 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)attn_smem;
 
     const int s = blockIdx.x;
-    const int kvh = blockIdx.y / p.wgp, wg = blockIdx.y % p.wgp;
+    // Row groups (wg) of one KV head read the same K/V.  Workgroups go to the 8 XCDs round-robin by linear id;
+    // with wg as the slow index the ids of one (split, KV head) differ by multiples of nsplit * Hkv, i.e. (for
+    // Hkv a multiple of 8) they share an XCD and the second reader of a K/V line finds it in that XCD's L2.
+    const int wg = blockIdx.y / p.Hkv, kvh = blockIdx.y % p.Hkv;
     const int b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -743,7 +746,7 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
 // ----------------------------------------------------------------------------------------------
 struct Plan {
     bool mfma;
-    int nw, pairs, wgp, chunk, nsplit;
+    int nw, ns, pairs, wgp, chunk, nsplit;
 };
 
 static bool supported(const etv_attn_desc *h) {
@@ -751,44 +754,59 @@ static bool supported(const etv_attn_desc *h) {
     return true;
 }
 
+// Launch shape.  Cost model in microseconds, fitted on MI355X: workgroups run in rounds of the slots the chip
+// offers; a round costs its tiles plus tree tiles and ramp-up; every extra split writes and re-reads one
+// (m, l, O) set per query row and needs the combine launch.  A tile costs about 2.8 us for an 8-wavefront
+// workgroup (two wavefronts per SIMD), the same for two 4-wavefront workgroups sharing a compute unit, and
+// about 1.7 us for a 4-wavefront workgroup that has a compute unit to itself.
 static Plan make_plan(const etv_attn_desc *h) {
     Plan pl{};
     const int tiles = max(1, (h->P_max + KT - 1) / KT);
+    const int B = max(1, h->B);
     pl.mfma = (h->dtype == ETV_BF16 && h->d == 128 && !(h->flags & ETV_ATTN_FLAG_GENERIC));
-    long units;
-    if (pl.mfma) {
-        const int nrc = (h->T_max + 31) / 32;        // 32-row chunks
-        pl.pairs = (h->Hq / h->Hkv) * nrc;           // (head in group, row chunk) pairs per KV head
-        pl.nw = pl.pairs > 4 ? 8 : 4;                // wavefronts per workgroup
-        pl.wgp = (pl.pairs + pl.nw - 1) / pl.nw;
-        units = (long)max(1, h->B) * h->Hkv * pl.wgp;
-    } else {
-        units = ((long)max(1, h->B) * h->Hq * h->T_max + 7) / 8;  // 8 resident wavefronts ~ one workgroup slot
+    if (!pl.mfma) {
+        const long units = ((long)B * h->Hq * h->T_max + 7) / 8;  // 8 resident wavefronts ~ one workgroup slot
+        int tps;
+        if (h->kv_split > 0) {
+            tps = (h->kv_split + KT - 1) / KT;
+        } else {
+            long want = (256 + units - 1) / units;
+            want = want < 1 ? 1 : (want > tiles ? tiles : want);
+            tps = (int)((tiles + want - 1) / want);
+        }
+        pl.chunk = tps * KT;
+        pl.nsplit = (tiles + tps - 1) / tps;
+        return pl;
     }
-    int tiles_per_split;
-    if (h->kv_split > 0) {
-        tiles_per_split = (h->kv_split + KT - 1) / KT;
-    } else {
-        // Pick the split count with a small cost model (microseconds, fitted on MI355X): workgroups run in
-        // rounds of 256 (one per compute unit; the small-tree kernel fits two), each round costs its tiles
-        // plus a tree tile and ramp-up; every extra split writes and re-reads one (m, l, O) set per query row.
-        const double t_tile = pl.mfma ? 2.8 : 6.0;
-        const double slots = (pl.mfma && pl.nw == 4) ? 512.0 : 256.0;
-        const double part_us = 2.0 * max(1, h->B) * h->Hq * h->T_max * (h->d + 2.0) * 4.0 / 3.0e6;
-        double best = 1e30;
-        int best_n = 1;
+    pl.pairs = (h->Hq / h->Hkv) * ((h->T_max + 31) / 32);  // (head in group, 32-row chunk) pairs per KV head
+    const double part_us = 2.0 * B * h->Hq * h->T_max * (h->d + 2.0) * 4.0 / 3.0e6;
+    double best = 1e30;
+    for (int nw = 4; nw <= 8; nw += 4) {
+        if (nw == 8 && (pl.pairs <= 4 || (h->flags & ETV_ATTN_FLAG_SMALL_WG))) continue;
+        const int wgp = (pl.pairs + nw - 1) / nw;
+        const long units = (long)B * h->Hkv * wgp;
         for (int ns = 1; ns <= tiles; ns++) {
             const int tps = (tiles + ns - 1) / ns;
-            const int n_eff = (tiles + tps - 1) / tps;
-            if (n_eff != ns) continue;
-            const double rounds = ceil((double)units * ns / slots);
-            const double est = rounds * (tps + 1.5) * t_tile + (ns > 1 ? 4.0 + ns * part_us : 0.0);
-            if (est < best) { best = est; best_n = ns; }
+            if ((tiles + tps - 1) / tps != ns) continue;
+            if (h->kv_split > 0 && tps != (h->kv_split + KT - 1) / KT) continue;
+            const long wgs = units * ns;
+            const bool alone = (nw == 4 && wgs <= 256);
+            const double slots = nw == 8 ? 256.0 : 512.0;
+            const double t_tile = alone ? 1.7 : 2.8;
+            const double rounds = ceil((double)wgs / slots);
+            const double est = rounds * (tps + 1.5) * t_tile + 4.0 + (ns > 1 ? 4.6 + ns * part_us : 0.0);
+            if (est < best) {
+                best = est;
+                pl.nw = nw; pl.wgp = wgp; pl.chunk = tps * KT; pl.nsplit = ns;
+                pl.ns = nw == 8 ? 4 : (alone ? 4 : 2);  // ring stages: a lone small workgroup can afford four
+            }
         }
-        tiles_per_split = (tiles + best_n - 1) / best_n;
     }
-    pl.chunk = tiles_per_split * KT;
-    pl.nsplit = (tiles + tiles_per_split - 1) / tiles_per_split;
+    if (best == 1e30) {  // kv_split larger than the prefix: a single split
+        pl.nw = (pl.pairs > 4 && !(h->flags & ETV_ATTN_FLAG_SMALL_WG)) ? 8 : 4;
+        pl.wgp = (pl.pairs + pl.nw - 1) / pl.nw;
+        pl.chunk = tiles * KT; pl.nsplit = 1; pl.ns = pl.nw == 8 ? 4 : 2;
+    }
     return pl;
 }
 
@@ -867,8 +885,9 @@ extern "C" int32_t etv_tree_verify_attention(const etv_attn_desc *h, const void 
         dim3 grid(pl.nsplit, h->Hkv * pl.wgp, h->B);
         const bool paged = h->block_size > 0;
         // 8 wavefronts: one workgroup per compute unit with a 4-stage ring (128 KiB of LDS);
-        // 4 wavefronts: two workgroups per compute unit with 2 stages each
+        // 4 wavefronts: two workgroups per compute unit with 2 stages each, or 4 stages when the grid is small
         if (pl.nw == 8) rc = paged ? launch_mfma<8, 4, true>(p, grid, st) : launch_mfma<8, 4, false>(p, grid, st);
+        else if (pl.ns == 4) rc = paged ? launch_mfma<4, 4, true>(p, grid, st) : launch_mfma<4, 4, false>(p, grid, st);
         else rc = paged ? launch_mfma<4, 2, true>(p, grid, st) : launch_mfma<4, 2, false>(p, grid, st);
     } else {
         dim3 grid(h->T_max, h->Hq, h->B * pl.nsplit);
