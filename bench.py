@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--kv-split", type=int, default=0)
     ap.add_argument("--attn-flags", type=int, default=0)
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one device copy of this many MiB (a known-size kernel to calibrate profiler byte counters)")
     ap.add_argument("--sets", type=int, default=0, help="cache sets to rotate over (0 = enough to exceed 640 MB)")
     return ap.parse_args()
 
@@ -205,6 +207,12 @@ def main():
     wl, desc_text = make_host_workload(a.workload)
     st = Step(wl, a.layers, a.sets, a.kv_split, a.attn_flags)
     tokens_per_step = int(wl.n_nodes.sum())
+    if a.calib_copy_mib > 0:
+        src = torch.ones(a.calib_copy_mib * 2 ** 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     if a.no_graph:
         runners = [(lambda s=s: st.run(s)) for s in range(st.nsets)]
@@ -248,7 +256,7 @@ def main():
         roof = {"bound": "mfma", "achieved": fl / (att_us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = None
-    tpath = os.path.join(ROOT, "profiles", f"attention_hbm_traffic_{a.workload}.json")
+    tpath = os.path.join(ROOT, "profiles", f"attention_hbm_traffic_{a.workload}.txt")
     if os.path.exists(tpath):
         roof["traffic"] = json.load(open(tpath)).get("hbm_bytes_per_launch")
     roof.update({"kernel": "tree_verify_attention (one layer: split-KV partial kernel + combine)",
