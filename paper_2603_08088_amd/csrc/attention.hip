@@ -27,7 +27,7 @@ struct AttnParams {
     int nsplit;  // splits the launch provides; sequence b uses max(1, ceil(P_b / chunk)) of them
     // partial results, split-major so that one workgroup writes one contiguous region:
     //   part_o [B][nsplit][Hq][T_max][d], part_m / part_l [B][nsplit][Hq][T_max]
-    int pairs;   // mfma kernel: (head-in-group, row chunk) pairs per KV head
+    int pairs;   // mfma kernel: 32-row chunks of the packed query rows of a KV head
     int wgp;     // mfma kernel: workgroups per (b, kv head, split) = ceil(pairs / 4)
     float scale_log2;
 };
@@ -252,7 +252,7 @@ __global__ void __launch_bounds__(D) attn_combine_kernel(AttnParams p) {
 // MFMA kernel (bf16, d = 128).
 //
 // Work unit: (split, KV head x row group, sequence).  A workgroup has NW wavefronts (8, or 4 for small
-// trees); wavefront w owns one (query head, 32-row chunk) pair and all of them share the K/V tiles of
+// trees); wavefront w owns one 32-row chunk of the KV head's packed query rows and all of them share the K/V tiles of
 // their KV head through LDS, so each prefix K/V byte is fetched from HBM once per G*T query rows.  Two
 // wavefronts are resident per SIMD: while one runs the softmax on the vector ALU the other feeds the
 // matrix cores.
@@ -569,12 +569,16 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     if (s >= nvalid) return;  // uniform over the workgroup
     const bool direct = (p.nsplit == 1);
 
+    // The G * T_max query rows of a KV head are numbered r = k * G + g (node k, head-in-group g) and cut into
+    // chunks of 32: a small tree fills whole MFMA tiles with rows of several heads instead of padding every
+    // head to 32 rows.  Wavefront `wave` of row group `wg` owns chunk `pair`.
     const int pair = wg * NW + wave;
     const bool active = pair < p.pairs;
-    const int g = active ? pair % p.G : 0;
-    const int rc = active ? pair / p.G : 0;
-    const int h = kvh * p.G + g;
-    const int kq = rc * 32 + c32;  // the lane's query row
+    const int r = (active ? pair : 0) * 32 + c32;
+    const int kq = r / p.G;              // the lane's node
+    const int h = kvh * p.G + (r - kq * p.G);  // and query head
+    // wavefront-uniform: does the chunk hold any valid row?  If not the wavefront only takes part in loads and barriers
+    const bool wactive = active && pair * 32 < n * p.G;
 
     const int k0 = s * p.chunk, k1 = min(P, k0 + p.chunk);
     const int nfull = (k1 > k0) ? (k1 - k0) / KT : 0;               // full prefix tiles
@@ -681,12 +685,14 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
         for (; ti < nfull; ti++) {  // full prefix tiles: no masking code at all
             ring_step(ti);
             const uint8_t *lk = smem + (ti % NS) * STAGE_BYTES;
+            if (!wactive) continue;
             qk_softmax<false>(tv, lk, qreg, oacc, m_run, l_run, p.scale_log2, ~0ull, pf);
             pv_accumulate(tv, lk + TILE_BYTES, pf, oacc, vf, false);
         }
         for (; ti < nt; ti++) {     // ragged last prefix tile and tree tiles
             ring_step(ti);
             const uint8_t *lk = smem + (ti % NS) * STAGE_BYTES;
+            if (!wactive) continue;
             qk_softmax<true>(tv, lk, qreg, oacc, m_run, l_run, p.scale_log2, tile_vis(ti), pf);
             pv_accumulate(tv, lk + TILE_BYTES, pf, oacc, vf, false);
         }
@@ -694,15 +700,17 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
         // one phase behind: PV(t-1), QK(t), softmax(t) within ring step t; the last PV after the loop
         for (; ti < nfull; ti++) {
             ring_step(ti);
+            if (!wactive) continue;
             if (ti > 0) pv_accumulate(tv, smem + ((ti - 1) % NS) * STAGE_BYTES + TILE_BYTES, pf, oacc, vf, false);
             qk_softmax<false>(tv, smem + (ti % NS) * STAGE_BYTES, qreg, oacc, m_run, l_run, p.scale_log2, ~0ull, pf);
         }
         for (; ti < nt; ti++) {
             ring_step(ti);
+            if (!wactive) continue;
             if (ti > 0) pv_accumulate(tv, smem + ((ti - 1) % NS) * STAGE_BYTES + TILE_BYTES, pf, oacc, vf, false);
             qk_softmax<true>(tv, smem + (ti % NS) * STAGE_BYTES, qreg, oacc, m_run, l_run, p.scale_log2, tile_vis(ti), pf);
         }
-        if (nt > 0) pv_accumulate(tv, smem + ((nt - 1) % NS) * STAGE_BYTES + TILE_BYTES, pf, oacc, vf, false);
+        if (nt > 0 && wactive) pv_accumulate(tv, smem + ((nt - 1) % NS) * STAGE_BYTES + TILE_BYTES, pf, oacc, vf, false);
     }
 
     // ---- epilogue
@@ -778,7 +786,7 @@ static Plan make_plan(const etv_attn_desc *h) {
         pl.nsplit = (tiles + tps - 1) / tps;
         return pl;
     }
-    pl.pairs = (h->Hq / h->Hkv) * ((h->T_max + 31) / 32);  // (head in group, 32-row chunk) pairs per KV head
+    pl.pairs = ((h->Hq / h->Hkv) * h->T_max + 31) / 32;  // 32-row chunks of the G * T_max packed rows of a KV head
     const double part_us = 2.0 * B * h->Hq * h->T_max * (h->d + 2.0) * 4.0 / 3.0e6;
     double best = 1e30;
     for (int nw = 4; nw <= 8; nw += 4) {
