@@ -216,16 +216,10 @@ __global__ void __launch_bounds__(D) attn_combine_kernel(AttnParams p) {
     const int nvalid = seq_nsplit(p, seq_prefix_len(p, b));
     const size_t pr0 = part_row(p, b, 0, h, k);
     const size_t sstride = (size_t)p.Hq * p.T_max;  // rows between consecutive splits
-    float M = -INFINITY;
+    // One pass: batches of eight splits, all of a batch's loads (m, l, O) in flight together, and a running
+    // (M, L, acc) that is rescaled when a later batch raises the maximum.
+    float M = -INFINITY, L = 0.f, acc = 0.f;
     for (int s0 = 0; s0 < nvalid; s0 += 8) {
-        float ms[8];
-#pragma unroll
-        for (int u = 0; u < 8; u++) ms[u] = (s0 + u < nvalid) ? p.part_m[pr0 + (size_t)(s0 + u) * sstride] : -INFINITY;
-#pragma unroll
-        for (int u = 0; u < 8; u++) M = fmaxf(M, ms[u]);
-    }
-    float L = 0.f, acc = 0.f;
-    for (int s0 = 0; s0 < nvalid; s0 += 8) {  // eight independent loads in flight per thread
         float ms[8], ls[8], os[8];
 #pragma unroll
         for (int u = 0; u < 8; u++) {
@@ -235,6 +229,14 @@ __global__ void __launch_bounds__(D) attn_combine_kernel(AttnParams p) {
             ls[u] = p.part_l[r];
             os[u] = p.part_o[r * D + c];
         }
+        float Mb = M;
+#pragma unroll
+        for (int u = 0; u < 8; u++) Mb = fmaxf(Mb, ms[u]);
+        if (Mb == -INFINITY) continue;  // nothing visible in this batch or before
+        const float keep = exp2f(M - Mb);  // 0 while M is still -inf
+        L *= keep;
+        acc *= keep;
+        M = Mb;
 #pragma unroll
         for (int u = 0; u < 8; u++) {
             if (ms[u] != -INFINITY) {  // absent or empty split: its l/O may be uninitialised memory
@@ -766,7 +768,8 @@ static bool supported(const etv_attn_desc *h) {
 // offers; a round costs its tiles plus tree tiles and ramp-up; every extra split writes and re-reads one
 // (m, l, O) set per query row and needs the combine launch.  A tile costs about 2.8 us for an 8-wavefront
 // workgroup (two wavefronts per SIMD), the same for two 4-wavefront workgroups sharing a compute unit, and
-// about 1.7 us for a 4-wavefront workgroup that has a compute unit to itself.
+// about 1.7 us for a 4-wavefront workgroup that has a compute unit to itself (1.5 us when at most two of its
+// wavefronts hold valid rows).
 static Plan make_plan(const etv_attn_desc *h) {
     Plan pl{};
     const int tiles = max(1, (h->P_max + KT - 1) / KT);
@@ -800,7 +803,7 @@ static Plan make_plan(const etv_attn_desc *h) {
             const long wgs = units * ns;
             const bool alone = (nw == 4 && wgs <= 256);
             const double slots = nw == 8 ? 256.0 : 512.0;
-            const double t_tile = alone ? 1.7 : 2.8;
+            const double t_tile = alone ? (pl.pairs <= 2 ? 1.5 : 1.7) : 2.8;
             const double rounds = ceil((double)wgs / slots);
             const double est = rounds * (tps + 1.5) * t_tile + 4.0 + (ns > 1 ? 4.6 + ns * part_us : 0.0);
             if (est < best) {
