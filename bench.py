@@ -249,6 +249,19 @@ def main():
     torch.cuda.synchronize()
     att_us = e0.elapsed_time(e1) * 1e3 / (reps * a.layers)
     by, fl = attention_algorithmic(wl)
+    # what plain streaming loads sustain on this machine (a 1 GiB buffer read by the library's probe kernel)
+    probe = torch.empty(2 ** 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
+    for _ in range(2):
+        api.hbm_read_probe(probe, sink)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
+        api.hbm_read_probe(probe, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    stream_gbs = 5 * probe.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del probe
     hbm_t, mfma_t = by / (HBM_PEAK_GBS * 1e9), fl / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     if hbm_t >= mfma_t:
         roof = {"bound": "hbm", "achieved": by / (att_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
@@ -261,7 +274,8 @@ def main():
         roof["traffic"] = json.load(open(tpath)).get("hbm_bytes_per_launch")
     roof.update({"kernel": "tree_verify_attention (one layer: split-KV partial kernel + combine)",
                  "avg_launch_us": att_us, "algorithmic_bytes": by, "algorithmic_flops": fl,
-                 "hbm_gbs": by / (att_us * 1e-6) / 1e9, "mfma_tflops": fl / (att_us * 1e-6) / 1e12})
+                 "hbm_gbs": by / (att_us * 1e-6) / 1e9, "mfma_tflops": fl / (att_us * 1e-6) / 1e12,
+                 "measured_stream_read_gbs": stream_gbs})
 
     cpu = None if a.skip_cpu else cpu_baseline(a.workload, a.layers)
     line = {

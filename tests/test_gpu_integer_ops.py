@@ -197,3 +197,15 @@ def test_commit_fully_accepted_chain_and_aliasing_prefix_len():
                                  prefix_len_out=plen)
     torch.cuda.synchronize()
     assert plen.item() == P + T and np.array_equal(bits_of(got["slot_map"]), ref["slot_map"])
+
+
+def test_hbm_read_probe_runs_and_rejects_bad_arguments():
+    buf = torch.ones(8 * 2 ** 20, dtype=torch.uint8, device="cuda:0")
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
+    api.hbm_read_probe(buf, sink)
+    torch.cuda.synchronize()
+    assert int(sink.sum().item()) == 0          # the probe only reads
+    with pytest.raises(api.EtvError):
+        api.hbm_read_probe(buf[: 2 ** 16], sink)   # below the 1 MiB minimum
+    with pytest.raises(api.EtvError):
+        api.hbm_read_probe(buf[1:], sink)          # misaligned
