@@ -134,6 +134,8 @@ typedef struct etv_attn_desc {
 
 #define ETV_ATTN_FLAG_GENERIC 1 /* run the fp32-VALU kernel even where the MFMA kernel applies (diagnostics) */
 #define ETV_ATTN_FLAG_SMALL_WG 2 /* always use 4-wavefront workgroups (tuning) */
+#define ETV_ATTN_FLAG_WHOLE_TILE 4 /* every wavefront takes whole 64-key tiles, never key halves (tuning) */
+#define ETV_ATTN_FLAG_KEY_HALVES 8 /* two wavefronts per 32-row chunk wherever the tree is small enough (tuning) */
 
 ETV_API size_t etv_tree_verify_attention_workspace_bytes(const etv_attn_desc *h_desc);
 

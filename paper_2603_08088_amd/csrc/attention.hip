@@ -337,8 +337,11 @@ __device__ __forceinline__ int vswz_of_row(int r) { return ((r & 3) << 1) | ((r 
 extern __shared__ __attribute__((aligned(1024))) uint8_t attn_smem[];
 
 // Asynchronous loads of one 64-key K/V tile into ring stage (ti % NS).  A tile is 16 chunk pairs of
-// 1 KiB (4 key rows of K, the same 4 rows of V).  Issuing wavefront w takes pairs w, w+4, ...; in a chunk lane i
-// fetches key row 4j + i/16 and the 16-byte piece that belongs at chunk position i%16 of that row.
+// 1 KiB (4 key rows of K, the same 4 rows of V).  Issuing wavefront w takes pairs w, w+4, w+8, w+12; in a chunk
+// lane i fetches key row 4j + i/16 and the 16-byte piece that belongs at chunk position i%16 of that row.
+// Pair w + 4u holds rows 16u + 4w .. +3: the lane's place within those 16 rows (and with it both swizzles)
+// does not depend on u, so a load is a scalar base per u plus one per-lane 32-bit offset, and the address
+// arithmetic of a tile is scalar (a wavefront's instruction issue rate is what bounds a tile step).
 template <int NW>
 struct TileLoader {
     // wavefronts that issue loads: all 4 of a small workgroup; of 8, only wavefronts 0..3, which otherwise
@@ -346,14 +349,19 @@ struct TileLoader {
     static constexpr int NI = 4;
     static constexpr int U = 16 / NI;  // chunk pairs per issuing wavefront and tile
     const uint8_t *kc, *vc, *kt, *vt;
+    const uint8_t *kf, *vf;  // full tiles: kc / vc advanced by head_off (paged) or seq_off (contiguous)
     const int32_t *bt;
-    size_t row_stride, seq_off, blk_stride, head_off;
+    size_t row_stride, seq_off, blk_stride, head_off;  // strides are below 2^32
     uint32_t smem_addr;
     int wave, l_row, l_pos, k0, k1, npt, n;
-    size_t lane_row_contig[U];   // per-lane row part of the source offset, contiguous cache
-    uint32_t lane_row_paged[U];  // same, paged cache (row within one block of one head)
-    uint32_t kcol[U], vcol[U];   // per-lane source column (bytes) for the K tile / the V tile swizzle
+    uint32_t kcol, vcol;  // per-lane source column (bytes) for the K tile / the V tile swizzle
+    uint32_t koff, voff;  // per-lane byte offset from the scalar base of a chunk pair (full tiles)
 };
+
+// 16 bytes per lane from (uniform base + per-lane 32-bit offset) into LDS at (lds_addr + 16 * lane)
+__device__ __forceinline__ void async_load16_s(const void *sbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n" ::"v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
 
 // full prefix tile (all 64 keys exist): straight-line address arithmetic.  For a paged cache the physical
 // block ids are fetched with scalar loads by fetch_blocks() ahead of the wait and barrier of the ring step,
@@ -369,24 +377,15 @@ __device__ __forceinline__ void fetch_blocks(const TileLoader<NW> &ld, int ti, i
 template <int NW, int NS, bool PAGED>
 __device__ __forceinline__ void issue_full_tile(const TileLoader<NW> &ld, int ti, const int (&blk)[TileLoader<NW>::U]) {
     constexpr int U = TileLoader<NW>::U, NI = TileLoader<NW>::NI;
-    const uint32_t stage = ld.smem_addr + (uint32_t)(ti % NS) * STAGE_BYTES;
-    if (PAGED) {
+    static_assert(NI == 4 && U == 4, "pair w + 4u lies in 16-key block u of the tile");
+    const uint32_t dst = ld.smem_addr + (uint32_t)(ti % NS) * STAGE_BYTES + (uint32_t)ld.wave * 1024;
 #pragma unroll
-        for (int u = 0; u < U; u++) {
-            const int j = ld.wave + NI * u;
-            const size_t off = (size_t)blk[u] * ld.blk_stride + ld.head_off + ld.lane_row_paged[u];
-            async_load16(ld.kc + off + ld.kcol[u], stage + j * 1024);
-            async_load16(ld.vc + off + ld.vcol[u], stage + TILE_BYTES + j * 1024);
-        }
-    } else {
-        const size_t tile_off = ld.seq_off + (size_t)(ld.k0 + ti * KT) * ld.row_stride;
-#pragma unroll
-        for (int u = 0; u < U; u++) {
-            const int j = ld.wave + NI * u;
-            const size_t off = tile_off + ld.lane_row_contig[u];
-            async_load16(ld.kc + off + ld.kcol[u], stage + j * 1024);
-            async_load16(ld.vc + off + ld.vcol[u], stage + TILE_BYTES + j * 1024);
-        }
+    for (int u = 0; u < U; u++) {
+        // kf / vf: the cache pointers advanced to this KV head's part of block 0 (paged) or of row 0 of the sequence
+        const size_t off = PAGED ? (size_t)(uint32_t)blk[u] * (size_t)(uint32_t)ld.blk_stride
+                                 : (size_t)(uint32_t)(ld.k0 + ti * KT + 16 * u) * (size_t)(uint32_t)ld.row_stride;
+        async_load16_s(ld.kf + off, ld.koff, dst + u * (NI * 1024));
+        async_load16_s(ld.vf + off, ld.voff, dst + TILE_BYTES + u * (NI * 1024));
     }
 }
 
@@ -416,8 +415,8 @@ __device__ __forceinline__ void issue_edge_tile(const TileLoader<NW> &ld, int ti
         } else {
             off = ld.seq_off + (size_t)key * ld.row_stride;
         }
-        async_load16(ksrc + off + ld.kcol[u], stage + j * 1024);
-        async_load16(vsrc + off + ld.vcol[u], stage + TILE_BYTES + j * 1024);
+        async_load16(ksrc + off + ld.kcol, stage + j * 1024);
+        async_load16(vsrc + off + ld.vcol, stage + TILE_BYTES + j * 1024);
     }
 }
 
@@ -548,7 +547,85 @@ __device__ __forceinline__ void pv_accumulate(const TileView &tv, const uint8_t 
     }
 }
 
-template <int NW, int NS, bool PAGED>
+// Key-halves variants: a wavefront takes 32 of the 64 keys of a tile (key block kb); two wavefronts share a
+// 32-row chunk and keep independent running (m, l, O), merged once after the last tile.  Halves the
+// per-tile dependency chain of a wavefront, which is what bounds the rate when a workgroup has fewer chunks
+// than wavefronts.  vis32: visibility bits of the wavefront's 32 keys.
+template <bool MASKED>
+__device__ __forceinline__ void qk_softmax_half(const TileView &tv, const uint8_t *lk, int kb, const bf16x8 (&qreg)[8],
+                                                f32x16 (&oacc)[4], float &m_run, float &l_run, float scale_log2,
+                                                uint32_t vis32, bf16x8 (&pf)[2]) {
+    // two accumulator chains over the even / odd 16-wide d steps, summed afterwards
+    f32x16 s0, s1;
+#pragma unroll
+    for (int i = 0; i < 16; i++) { s0[i] = 0.f; s1[i] = 0.f; }
+    {
+        bf16x8 ka[8];
+        const uint8_t *kr = lk + tv.krow + kb * (32 * ROW_BYTES);
+#pragma unroll
+        for (int kk = 0; kk < 8; kk++)
+            ka[kk] = *reinterpret_cast<const bf16x8 *>(kr + (((2 * kk + tv.hh) ^ tv.ksw) << 4));
+#pragma unroll
+        for (int kk = 0; kk < 8; kk += 2) {
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qreg[kk], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk + 1], qreg[kk + 1], s1, 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 16; i++) s0[i] += s1[i];
+    if (MASKED) {
+        const uint32_t lo = vis32 >> (4 * tv.hh);
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int bit = 8 * (i >> 2) + (i & 3);
+            s0[i] = ((lo >> bit) & 1u) ? s0[i] : -INFINITY;
+        }
+    }
+    float rmax = max3(s0[0], s0[1], s0[2]);
+#pragma unroll
+    for (int i = 3; i < 15; i += 2) rmax = max3(rmax, s0[i], s0[i + 1]);
+    rmax = fmaxf(rmax, s0[15]);
+    rmax = half_swap_max(rmax);
+    const float tmax = rmax * scale_log2;
+    const bool lift = tmax > m_run + kLazy;
+    if (__any(lift)) {
+        const float m_new = lift ? tmax : m_run;
+        const float alpha = lift ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < 4; db++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) oacc[db][i] *= alpha;
+    }
+    const float neg_m = (MASKED && m_run == -INFINITY) ? 0.f : -m_run;
+    float psum = 0.f;
+    uint32_t pk[8];
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+        const float a0 = __builtin_amdgcn_exp2f(fmaf(s0[i], scale_log2, neg_m));
+        const float a1 = __builtin_amdgcn_exp2f(fmaf(s0[i + 1], scale_log2, neg_m));
+        psum += a0 + a1;
+        pk[i >> 1] = pack_bf16x2(a0, a1);
+    }
+    const uint4 l0 = {pk[0], pk[1], pk[2], pk[3]}, h0 = {pk[4], pk[5], pk[6], pk[7]};
+    pf[0] = __builtin_bit_cast(bf16x8, l0);
+    pf[1] = __builtin_bit_cast(bf16x8, h0);
+    l_run += psum;
+}
+
+__device__ __forceinline__ void pv_accumulate_half(const TileView &tv, const uint8_t *lv, int kb, const bf16x8 (&pf)[2],
+                                                   f32x16 (&oacc)[4]) {
+    bf16x8 vf[2][4];
+    load_v_frags(tv, lv, kb, vf);
+#pragma unroll
+    for (int st = 0; st < 2; st++)
+#pragma unroll
+        for (int db = 0; db < 4; db++)
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st][db], pf[st], oacc[db], 0, 0, 0);
+}
+
+template <int NW, int NS, bool PAGED, bool KH>
 __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     constexpr int D = 128;
     constexpr int LPW = 2 * TileLoader<NW>::U;  // direct-to-LDS loads an issuing wavefront issues per tile
@@ -565,16 +642,60 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c32 = lane & 31, hh = lane >> 5;
 
-    const int n = clampi(p.n_nodes[b], 0, p.T_max);
-    const int P = seq_prefix_len(p, b);
+    // Start-up.  The caches are cold when a kernel starts and every dependent trip to memory costs the better
+    // part of a microsecond, so the trips before the first tile load are made as few as possible: one for the
+    // kernel arguments (all of them, not a few at a time as they come up), one for the sequence's sizes
+    // together with the physical block ids of the first tiles.  Those ids are read before it is known how long
+    // the prefix is: the index is clamped into the table row, and an id is used only if its tile turns out to
+    // be a full prefix tile.
+    constexpr bool kShifted = (NW == 8);
+    constexpr int PD = kShifted ? NS - 2 : NS - 1;  // tiles in flight behind the one being consumed
+    static_assert(PD >= 1 && PD <= 3, "ring depth");
+    asm volatile("" ::"s"(p.q), "s"(p.k_cache), "s"(p.v_cache), "s"(p.kt), "s"(p.vt), "s"(p.block_table),
+                 "s"(p.prefix_len), "s"(p.n_nodes), "s"(p.bitmask), "s"(p.T_max), "s"(p.Hq), "s"(p.G),
+                 "s"(p.max_blocks), "s"(p.P_cap), "s"(p.P_max), "s"(p.words), "s"(p.chunk), "s"(p.pairs));
+    const int n_raw = ((const_i32_ptr)(uintptr_t)p.n_nodes)[b], P_raw = ((const_i32_ptr)(uintptr_t)p.prefix_len)[b];
+    // (an issuing wavefront needs ids lb, lb+1, lb+2, lb+3 of each tile: 4 * PD consecutive table entries)
+    static_assert(TileLoader<NW>::U == 4 && TileLoader<NW>::NI == 4, "block ids of a tile: four consecutive entries");
+    int blk_pro[PD][4];
+    const int lb_first = (s * p.chunk) >> 4;
+    const bool spec = PAGED && lb_first + 4 * PD <= p.max_blocks;  // the whole range lies inside the table row
+    if (spec) {
+        const const_i32_ptr bt_row = (const_i32_ptr)(uintptr_t)(p.block_table + (size_t)b * p.max_blocks + lb_first);
+#pragma unroll
+        for (int t = 0; t < PD; t++)
+#pragma unroll
+            for (int u = 0; u < 4; u++) blk_pro[t][u] = bt_row[4 * t + u];
+    } else {
+#pragma unroll
+        for (int t = 0; t < PD; t++)
+#pragma unroll
+            for (int u = 0; u < 4; u++) blk_pro[t][u] = 0;
+    }
+    // one wait for all of them
+    if constexpr (PD == 3)
+        asm volatile("" ::"s"(n_raw), "s"(P_raw), "s"(blk_pro[0][0]), "s"(blk_pro[0][1]), "s"(blk_pro[0][2]), "s"(blk_pro[0][3]),
+                     "s"(blk_pro[1][0]), "s"(blk_pro[1][1]), "s"(blk_pro[1][2]), "s"(blk_pro[1][3]),
+                     "s"(blk_pro[2][0]), "s"(blk_pro[2][1]), "s"(blk_pro[2][2]), "s"(blk_pro[2][3]));
+    else if constexpr (PD == 2)
+        asm volatile("" ::"s"(n_raw), "s"(P_raw), "s"(blk_pro[0][0]), "s"(blk_pro[0][1]), "s"(blk_pro[0][2]), "s"(blk_pro[0][3]),
+                     "s"(blk_pro[1][0]), "s"(blk_pro[1][1]), "s"(blk_pro[1][2]), "s"(blk_pro[1][3]));
+    else
+        asm volatile("" ::"s"(n_raw), "s"(P_raw), "s"(blk_pro[0][0]), "s"(blk_pro[0][1]), "s"(blk_pro[0][2]), "s"(blk_pro[0][3]));
+
+    const int n = clampi(n_raw, 0, p.T_max);
+    const int P = clampi(P_raw, 0, p.P_max);
     const int nvalid = seq_nsplit(p, P);
     if (s >= nvalid) return;  // uniform over the workgroup
     const bool direct = (p.nsplit == 1);
 
     // The G * T_max query rows of a KV head are numbered r = k * G + g (node k, head-in-group g) and cut into
     // chunks of 32: a small tree fills whole MFMA tiles with rows of several heads instead of padding every
-    // head to 32 rows.  Wavefront `wave` of row group `wg` owns chunk `pair`.
-    const int pair = wg * NW + wave;
+    // head to 32 rows.  Wavefront `wave` of row group `wg` owns chunk `pair`; with key halves (KH) a chunk
+    // belongs to two wavefronts, wave and wave + NW/2, which take key block kb = 0 / 1 of every tile.
+    constexpr int CW = KH ? NW / 2 : NW;  // chunks per workgroup
+    const int kb = KH ? wave / CW : 0;
+    const int pair = wg * CW + (KH ? wave % CW : wave);
     const bool active = pair < p.pairs;
     const int r = (active ? pair : 0) * 32 + c32;
     const int kq = r / p.G;              // the lane's node
@@ -597,30 +718,30 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     ld.seq_off = ((size_t)b * p.P_cap * p.Hkv + kvh) * ROW_BYTES;   // contiguous cache: row 0 of (b, kvh)
     ld.blk_stride = (size_t)p.Hkv * 16 * ROW_BYTES;                  // paged cache: one block, all heads
     ld.head_off = (size_t)kvh * 16 * ROW_BYTES;
+    ld.kf = ld.kc + (PAGED ? ld.head_off : ld.seq_off); ld.vf = ld.vc + (PAGED ? ld.head_off : ld.seq_off);
     ld.smem_addr = smem_addr; ld.wave = wave; ld.l_row = lane >> 4; ld.l_pos = lane & 15;
     ld.k0 = k0; ld.k1 = k1; ld.npt = npt; ld.n = n;
-#pragma unroll
-    for (int u = 0; u < TileLoader<NW>::U; u++) {
-        const int r_in = 4 * (wave + TileLoader<NW>::NI * u) + ld.l_row;
-        ld.kcol[u] = (uint32_t)((ld.l_pos ^ kswz_of_row(r_in)) * 16);
-        ld.vcol[u] = (uint32_t)((ld.l_pos ^ vswz_of_row(r_in)) * 16);
-        ld.lane_row_contig[u] = (size_t)r_in * ld.row_stride;
-        ld.lane_row_paged[u] = (uint32_t)((r_in & 15) * ROW_BYTES);
+    {
+        // the lane's row within the 16 rows that pair `wave` + 4u covers, the same for every u
+        const int r_in = 4 * wave + ld.l_row;
+        ld.kcol = (uint32_t)((ld.l_pos ^ kswz_of_row(r_in)) * 16);
+        ld.vcol = (uint32_t)((ld.l_pos ^ vswz_of_row(r_in)) * 16);
+        const uint32_t rowpart = PAGED ? (uint32_t)((r_in & 15) * ROW_BYTES) : (uint32_t)r_in * (uint32_t)ld.row_stride;
+        ld.koff = rowpart + ld.kcol;
+        ld.voff = rowpart + ld.vcol;
     }
     const bool issuer = wave < TileLoader<NW>::NI;
-    auto issue = [&](int ti) {
-        if (!issuer) return;
-        if (ti < nfull) {
-            int blk[TileLoader<NW>::U];
-            if (PAGED) fetch_blocks<NW>(ld, ti, blk);
-            issue_full_tile<NW, NS, PAGED>(ld, ti, blk);
+    // prologue: fill the ring, then fetch Q and the mask row while those loads fly
+#pragma unroll
+    for (int t = 0; t < PD; t++) {
+        if (t >= nt || !issuer) continue;
+        if (t < nfull) {
+            if (PAGED && !spec) fetch_blocks<NW>(ld, t, blk_pro[t]);
+            issue_full_tile<NW, NS, PAGED>(ld, t, blk_pro[t]);
         } else {
-            issue_edge_tile<NW, NS>(ld, ti);
+            issue_edge_tile<NW, NS>(ld, t);
         }
-    };
-
-    // prologue: fill NS-1 stages, then fetch Q and the mask row while those loads fly
-    for (int ti = 0; ti < ((NW == 8) ? NS - 2 : NS - 1) && ti < nt; ti++) issue(ti);
+    }
 
     const uint16_t *qp = static_cast<const uint16_t *>(p.q);
     // Q as B operand: lane holds query row kq, d values 16*kk + 8*hh .. +7
@@ -659,9 +780,6 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     // Ring step: wait for tile ti, barrier, refill.  PD = tiles in flight behind the one being consumed.
     // With 8 wavefronts the V tile of step ti-1 is still being read by wavefronts 4..7 during step ti, so
     // the stage that is refilled is the one of tile ti-2.
-    constexpr bool kShifted = (NW == 8);
-    constexpr int PD = kShifted ? NS - 2 : NS - 1;
-    static_assert(PD >= 1 && PD <= 3, "ring depth");
     auto ring_step = [&](int ti) {
         const int tn = ti + PD;  // tile to issue in this step
         int blk[TileLoader<NW>::U];
@@ -681,38 +799,89 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
         return (ti - npt) ? mbits1 : mbits0;                            // tree tile: the row's ancestor bits
     };
     bf16x8 pf[2][2], vf[2][4];
+    // one tile for one wavefront, in two parts (the parts run in different ring steps for late wavefronts)
+    auto part_qk = [&](int t, bool masked) {
+        const uint8_t *lk = smem + (t % NS) * STAGE_BYTES;
+        if (KH) {
+            const uint32_t v32 = masked ? (uint32_t)(tile_vis(t) >> (32 * kb)) : ~0u;
+            if (masked) qk_softmax_half<true>(tv, lk, kb, qreg, oacc, m_run, l_run, p.scale_log2, v32, pf[0]);
+            else qk_softmax_half<false>(tv, lk, kb, qreg, oacc, m_run, l_run, p.scale_log2, v32, pf[0]);
+        } else {
+            if (masked) qk_softmax<true>(tv, lk, qreg, oacc, m_run, l_run, p.scale_log2, tile_vis(t), pf);
+            else qk_softmax<false>(tv, lk, qreg, oacc, m_run, l_run, p.scale_log2, ~0ull, pf);
+        }
+    };
+    auto part_pv = [&](int t) {
+        const uint8_t *lv = smem + (t % NS) * STAGE_BYTES + TILE_BYTES;
+        if (KH) pv_accumulate_half(tv, lv, kb, pf[0], oacc);
+        else pv_accumulate(tv, lv, pf, oacc, vf, false);
+    };
     int ti = 0;
     if (!kShifted || wave < 4) {
         // QK(t), softmax(t), PV(t) within ring step t
         for (; ti < nfull; ti++) {  // full prefix tiles: no masking code at all
             ring_step(ti);
-            const uint8_t *lk = smem + (ti % NS) * STAGE_BYTES;
             if (!wactive) continue;
-            qk_softmax<false>(tv, lk, qreg, oacc, m_run, l_run, p.scale_log2, ~0ull, pf);
-            pv_accumulate(tv, lk + TILE_BYTES, pf, oacc, vf, false);
+            part_qk(ti, false);
+            part_pv(ti);
         }
         for (; ti < nt; ti++) {     // ragged last prefix tile and tree tiles
             ring_step(ti);
-            const uint8_t *lk = smem + (ti % NS) * STAGE_BYTES;
             if (!wactive) continue;
-            qk_softmax<true>(tv, lk, qreg, oacc, m_run, l_run, p.scale_log2, tile_vis(ti), pf);
-            pv_accumulate(tv, lk + TILE_BYTES, pf, oacc, vf, false);
+            part_qk(ti, true);
+            part_pv(ti);
         }
     } else {
         // one phase behind: PV(t-1), QK(t), softmax(t) within ring step t; the last PV after the loop
         for (; ti < nfull; ti++) {
             ring_step(ti);
             if (!wactive) continue;
-            if (ti > 0) pv_accumulate(tv, smem + ((ti - 1) % NS) * STAGE_BYTES + TILE_BYTES, pf, oacc, vf, false);
-            qk_softmax<false>(tv, smem + (ti % NS) * STAGE_BYTES, qreg, oacc, m_run, l_run, p.scale_log2, ~0ull, pf);
+            if (ti > 0) part_pv(ti - 1);
+            part_qk(ti, false);
         }
         for (; ti < nt; ti++) {
             ring_step(ti);
             if (!wactive) continue;
-            if (ti > 0) pv_accumulate(tv, smem + ((ti - 1) % NS) * STAGE_BYTES + TILE_BYTES, pf, oacc, vf, false);
-            qk_softmax<true>(tv, smem + (ti % NS) * STAGE_BYTES, qreg, oacc, m_run, l_run, p.scale_log2, tile_vis(ti), pf);
+            if (ti > 0) part_pv(ti - 1);
+            part_qk(ti, true);
         }
-        if (nt > 0 && wactive) pv_accumulate(tv, smem + ((nt - 1) % NS) * STAGE_BYTES + TILE_BYTES, pf, oacc, vf, false);
+        if (nt > 0 && wactive) part_pv(nt - 1);
+    }
+
+    if (KH) {
+        // Merge the two key halves of a chunk through LDS (the ring is no longer needed): the kb = 1
+        // wavefront hands its (m, l, O) to its kb = 0 partner, which rescales both to the larger reference.
+        __builtin_amdgcn_s_barrier();  // every wavefront has finished reading tiles; no tile load is outstanding
+        asm volatile("" ::: "memory");
+        float4 *mx = reinterpret_cast<float4 *>(smem) + (size_t)(wave % CW) * (17 * 64);
+        if (kb == 1 && wactive) {
+#pragma unroll
+            for (int db = 0; db < 4; db++)
+#pragma unroll
+                for (int ig = 0; ig < 4; ig++)
+                    mx[(4 * db + ig) * 64 + lane] = float4{oacc[db][4 * ig], oacc[db][4 * ig + 1], oacc[db][4 * ig + 2], oacc[db][4 * ig + 3]};
+            mx[16 * 64 + lane] = float4{m_run, l_run, 0.f, 0.f};
+        }
+        __syncthreads();
+        if (kb == 1) return;
+        if (wactive) {
+            const float4 ml = mx[16 * 64 + lane];
+            const float m_new = fmaxf(m_run, ml.x);
+            const float fa = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run - m_new);
+            const float fb = (ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml.x - m_new);
+            m_run = m_new;
+            l_run = l_run * fa + ml.y * fb;
+#pragma unroll
+            for (int db = 0; db < 4; db++)
+#pragma unroll
+                for (int ig = 0; ig < 4; ig++) {
+                    const float4 o = mx[(4 * db + ig) * 64 + lane];
+                    oacc[db][4 * ig] = oacc[db][4 * ig] * fa + o.x * fb;
+                    oacc[db][4 * ig + 1] = oacc[db][4 * ig + 1] * fa + o.y * fb;
+                    oacc[db][4 * ig + 2] = oacc[db][4 * ig + 2] * fa + o.z * fb;
+                    oacc[db][4 * ig + 3] = oacc[db][4 * ig + 3] * fa + o.w * fb;
+                }
+        }
     }
 
     // ---- epilogue
@@ -755,12 +924,13 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
 // host side
 // ----------------------------------------------------------------------------------------------
 struct Plan {
-    bool mfma;
+    bool mfma, kh;
     int nw, ns, pairs, wgp, chunk, nsplit;
 };
 
 static bool supported(const etv_attn_desc *h) {
     if (h->B < 0 || h->T_max < 1 || h->Hq < 1 || h->Hkv < 1 || h->d < 1) return false;
+    if (h->Hq > 65536) return false;  // keeps the byte strides of a cache row and of a block below 2^32
     return true;
 }
 
@@ -770,6 +940,7 @@ static bool supported(const etv_attn_desc *h) {
 // workgroup (two wavefronts per SIMD), the same for two 4-wavefront workgroups sharing a compute unit, and
 // about 1.7 us for a 4-wavefront workgroup that has a compute unit to itself (1.5 us when at most two of its
 // wavefronts hold valid rows).
+constexpr double kTileKhAlone = 1.0, kTileKhShared = 1.8, kTileKh8 = 1.6;
 static Plan make_plan(const etv_attn_desc *h) {
     Plan pl{};
     const int tiles = max(1, (h->P_max + KT - 1) / KT);
@@ -793,43 +964,52 @@ static Plan make_plan(const etv_attn_desc *h) {
     const double part_us = 2.0 * B * h->Hq * h->T_max * (h->d + 2.0) * 4.0 / 3.0e6;
     double best = 1e30;
     for (int nw = 4; nw <= 8; nw += 4) {
-        if (nw == 8 && (pl.pairs <= 4 || (h->flags & ETV_ATTN_FLAG_SMALL_WG))) continue;
-        const int wgp = (pl.pairs + nw - 1) / nw;
-        const long units = (long)B * h->Hkv * wgp;
-        for (int ns = 1; ns <= tiles; ns++) {
-            const int tps = (tiles + ns - 1) / ns;
-            if ((tiles + tps - 1) / tps != ns) continue;
-            if (h->kv_split > 0 && tps != (h->kv_split + KT - 1) / KT) continue;
-            const long wgs = units * ns;
-            const bool alone = (nw == 4 && wgs <= 256);
-            const double slots = nw == 8 ? 256.0 : 512.0;
-            const double t_tile = alone ? (pl.pairs <= 2 ? 1.5 : 1.7) : 2.8;
-            const double rounds = ceil((double)wgs / slots);
-            const double est = rounds * (tps + 1.5) * t_tile + 4.0 + (ns > 1 ? 4.6 + ns * part_us : 0.0);
-            if (est < best) {
-                best = est;
-                pl.nw = nw; pl.wgp = wgp; pl.chunk = tps * KT; pl.nsplit = ns;
-                pl.ns = nw == 8 ? 4 : (alone ? 4 : 2);  // ring stages: a lone small workgroup can afford four
+        for (int kh = 0; kh <= 1; kh++) {
+            const int cw = kh ? nw / 2 : nw;  // chunks per workgroup
+            // key halves pay when a workgroup would otherwise have idle wavefronts
+            if (kh && (h->flags & ETV_ATTN_FLAG_WHOLE_TILE)) continue;
+            if (!kh && (h->flags & ETV_ATTN_FLAG_KEY_HALVES)) continue;
+            if (nw == 8 && (pl.pairs <= (kh ? 2 : 4) || (h->flags & ETV_ATTN_FLAG_SMALL_WG))) continue;
+            const int wgp = (pl.pairs + cw - 1) / cw;
+            const long units = (long)B * h->Hkv * wgp;
+            for (int ns = 1; ns <= tiles; ns++) {
+                const int tps = (tiles + ns - 1) / ns;
+                if ((tiles + tps - 1) / tps != ns) continue;
+                if (h->kv_split > 0 && tps != (h->kv_split + KT - 1) / KT) continue;
+                const long wgs = units * ns;
+                const bool alone = (nw == 4 && wgs <= 256);
+                const double slots = nw == 8 ? 256.0 : 512.0;
+                double t_tile;
+                if (kh) t_tile = alone ? kTileKhAlone : (nw == 8 ? kTileKh8 : kTileKhShared);
+                else t_tile = alone ? (pl.pairs <= 2 ? 1.5 : 1.7) : 2.8;
+                const double rounds = ceil((double)wgs / slots);
+                const double est = rounds * (tps + 1.5) * t_tile + 4.0 + (ns > 1 ? 4.6 + ns * part_us : 0.0);
+                if (est < best) {
+                    best = est;
+                    pl.nw = nw; pl.kh = kh; pl.wgp = wgp; pl.chunk = tps * KT; pl.nsplit = ns;
+                    pl.ns = nw == 8 ? 4 : (alone ? 4 : 2);  // ring stages: a lone small workgroup can afford four
+                }
             }
         }
     }
     if (best == 1e30) {  // kv_split larger than the prefix: a single split
         pl.nw = (pl.pairs > 4 && !(h->flags & ETV_ATTN_FLAG_SMALL_WG)) ? 8 : 4;
+        pl.kh = false;
         pl.wgp = (pl.pairs + pl.nw - 1) / pl.nw;
         pl.chunk = tiles * KT; pl.nsplit = 1; pl.ns = pl.nw == 8 ? 4 : 2;
     }
     return pl;
 }
 
-template <int NW, int NS, bool PAGED>
+template <int NW, int NS, bool PAGED, bool KH>
 static int32_t launch_mfma(const AttnParams &p, dim3 grid, hipStream_t st) {
     constexpr size_t lds = (size_t)NS * STAGE_BYTES;
     static const bool lds_ok = [] {  // opt in to more than 64 KiB of dynamic LDS, once per process
-        return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<NW, NS, PAGED>),
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<NW, NS, PAGED, KH>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
     }();
     if (!lds_ok) return ETV_ERR_HIP;
-    hipLaunchKernelGGL((attn_mfma_kernel<NW, NS, PAGED>), grid, dim3(NW * 64), lds, st, p);
+    hipLaunchKernelGGL((attn_mfma_kernel<NW, NS, PAGED, KH>), grid, dim3(NW * 64), lds, st, p);
     return check_launch();
 }
 
@@ -897,9 +1077,21 @@ extern "C" int32_t etv_tree_verify_attention(const etv_attn_desc *h, const void 
         const bool paged = h->block_size > 0;
         // 8 wavefronts: one workgroup per compute unit with a 4-stage ring (128 KiB of LDS);
         // 4 wavefronts: two workgroups per compute unit with 2 stages each, or 4 stages when the grid is small
-        if (pl.nw == 8) rc = paged ? launch_mfma<8, 4, true>(p, grid, st) : launch_mfma<8, 4, false>(p, grid, st);
-        else if (pl.ns == 4) rc = paged ? launch_mfma<4, 4, true>(p, grid, st) : launch_mfma<4, 4, false>(p, grid, st);
-        else rc = paged ? launch_mfma<4, 2, true>(p, grid, st) : launch_mfma<4, 2, false>(p, grid, st);
+        const int shape = (pl.nw == 8 ? 0 : (pl.ns == 4 ? 1 : 2)) * 4 + (paged ? 2 : 0) + (pl.kh ? 1 : 0);
+        switch (shape) {
+        case 0: rc = launch_mfma<8, 4, false, false>(p, grid, st); break;
+        case 1: rc = launch_mfma<8, 4, false, true>(p, grid, st); break;
+        case 2: rc = launch_mfma<8, 4, true, false>(p, grid, st); break;
+        case 3: rc = launch_mfma<8, 4, true, true>(p, grid, st); break;
+        case 4: rc = launch_mfma<4, 4, false, false>(p, grid, st); break;
+        case 5: rc = launch_mfma<4, 4, false, true>(p, grid, st); break;
+        case 6: rc = launch_mfma<4, 4, true, false>(p, grid, st); break;
+        case 7: rc = launch_mfma<4, 4, true, true>(p, grid, st); break;
+        case 8: rc = launch_mfma<4, 2, false, false>(p, grid, st); break;
+        case 9: rc = launch_mfma<4, 2, false, true>(p, grid, st); break;
+        case 10: rc = launch_mfma<4, 2, true, false>(p, grid, st); break;
+        default: rc = launch_mfma<4, 2, true, true>(p, grid, st); break;
+        }
     } else {
         dim3 grid(h->T_max, h->Hq, h->B * pl.nsplit);
         if (h->dtype == ETV_F32 && h->d == 64)
