@@ -8,7 +8,7 @@ with every input already resident in HBM.  The step is captured once into a HIP 
 set and replayed; cache sets are rotated so that consecutive steps stream K/V from HBM, not from
 the 256 MB memory-side cache.  Prints ONE JSON line (metric: tree-verify tokens/s).
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5_T<T>_D<D>] [--layers L]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c2_paged|c3|c4|c5_T<T>_D<D>[_B<B>_P<P>]] [--layers L]
                   [--no-graph] [--skip-cpu] [--kv-split N]
 """
 from __future__ import annotations
@@ -54,10 +54,11 @@ def make_host_workload(name):
         return synth.config3(with_cache=False), "ragged batch: B=8, P~U[512,8192], paged, 60-node trees"
     if name == "c4":
         return synth.config4(with_cache=False), "long context: B=1, P=32768, 128-node tree"
-    m = re.fullmatch(r"c5_T(\d+)_D(\d+)", name)
+    m = re.fullmatch(r"c5_T(\d+)_D(\d+)(?:_B(\d+)_P(\d+))?", name)
     if m:
-        return synth.config5(int(m.group(1)), int(m.group(2)), with_cache=False), \
-            f"budget sweep cell: B=32, P=4096 paged, T={m.group(1)}, depth {m.group(2)}"
+        B, P = int(m.group(3) or 32), int(m.group(4) or 4096)
+        return synth.config5(int(m.group(1)), int(m.group(2)), B=B, P=P, with_cache=False), \
+            f"budget sweep cell: B={B}, P={P} paged, T={m.group(1)}, depth {m.group(2)}"
     raise SystemExit(f"unknown workload {name}")
 
 

@@ -23,6 +23,9 @@ F32, BF16 = 0, 1
 TREE_RANGE, TREE_CYCLE, TREE_CLOSURE = 1, 2, 4
 COMMIT_CAPACITY, COMMIT_BAD_NODE, COMMIT_BAD_LEN, COMMIT_BAD_BLOCK = 1, 2, 4, 8
 ATTN_FLAG_GENERIC = 1
+ATTN_FLAG_SMALL_WG = 2
+ATTN_FLAG_WHOLE_TILE = 4
+ATTN_FLAG_KEY_HALVES = 8
 MAX_TREE, ATTN_MAX_TREE = 256, 128
 
 EXPORTS = ("etv_status_string", "etv_version", "etv_last_hip_error", "etv_hbm_read_probe", "etv_build_tree_mask",

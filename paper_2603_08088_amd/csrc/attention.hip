@@ -940,7 +940,7 @@ static bool supported(const etv_attn_desc *h) {
 // workgroup (two wavefronts per SIMD), the same for two 4-wavefront workgroups sharing a compute unit, and
 // about 1.7 us for a 4-wavefront workgroup that has a compute unit to itself (1.5 us when at most two of its
 // wavefronts hold valid rows).
-constexpr double kTileKhAlone = 1.0, kTileKhShared = 1.8, kTileKh8 = 1.6;
+constexpr double kTileKhAlone = 1.1, kTileKhShared = 2.2, kTileKh8 = 1.65;
 static Plan make_plan(const etv_attn_desc *h) {
     Plan pl{};
     const int tiles = max(1, (h->P_max + KT - 1) / KT);

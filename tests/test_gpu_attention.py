@@ -92,6 +92,43 @@ def test_mfma_kernel_grouping_ragged_and_edge_prefixes(paged, G, Hkv):
     _check(wl4, kv_split=64)
 
 
+@pytest.mark.parametrize("flags", [api.ATTN_FLAG_KEY_HALVES, api.ATTN_FLAG_WHOLE_TILE,
+                                   api.ATTN_FLAG_KEY_HALVES | api.ATTN_FLAG_SMALL_WG])
+@pytest.mark.parametrize("paged", [False, True])
+def test_mfma_kernel_key_halves_and_whole_tiles_agree_with_the_oracle(flags, paged):
+    """Both ways of sharing a tile among wavefronts (two wavefronts per 32-row chunk, each with half of the
+    tile's keys and a merge at the end; or one wavefront per chunk) on trees from 1 node up, ragged node
+    counts, prefixes around the 32- and 64-key boundaries, several tiles, flat and peaked softmaxes."""
+    rng = np.random.default_rng(1700 + flags + 100 * paged)
+    for T in (1, 3, 8, 9, 16, 24, 32, 40, 64):
+        wl = _small(rng, 2, T, 8, 2, 128, [300, 77], "bf16", paged, n_nodes=[T, max(1, T // 2)])
+        _check(wl, flags=flags)
+        _check(wl, kv_split=64, flags=flags)
+    P = [0, 1, 31, 32, 33, 63, 64, 65, 95, 96, 97, 500]
+    wl = _small(rng, len(P), 16, 8, 2, 128, P, "bf16", paged, n_nodes=[16, 1, 7, 16, 9, 16, 2, 16, 16, 5, 16, 11])
+    _check(wl, flags=flags)
+    _check(wl, kv_split=128, flags=flags)
+    for G, Hkv in ((1, 4), (8, 1)):
+        wl = _small(rng, 2, 12, G * Hkv, Hkv, 128, [700, 130], "bf16", paged, q_scale=4.0)
+        _check(wl, flags=flags)
+        _check(wl, kv_split=192, flags=flags)
+    wl = _small(rng, 2, 32, 8, 2, 128, [3000, 1537], "bf16", paged, q_scale=12.0)   # long, very peaked: many rescales
+    _check(wl, kv_split=4096, flags=flags)
+    _check(wl, kv_split=1024, flags=flags)
+
+
+def test_key_halves_merge_is_deterministic():
+    """The merge of the two key halves has a fixed order: two launches on the same inputs give the same bits."""
+    rng = np.random.default_rng(1800)
+    wl = _small(rng, 3, 16, 8, 2, 128, [300, 77, 640], "bf16", True, n_nodes=[16, 5, 16])
+    d = DevWorkload(wl)
+    m = api.build_tree_mask(d.parent, d.n_nodes)
+    out, lse = gpu_attention(d, m["bitmask"], kv_split=128, flags=api.ATTN_FLAG_KEY_HALVES)
+    out2, lse2 = gpu_attention(d, m["bitmask"], kv_split=128, flags=api.ATTN_FLAG_KEY_HALVES)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2) and torch.equal(lse, lse2)   # run-to-run deterministic
+
+
 def test_no_leak_from_hidden_tree_rows_padding_and_stale_cache_bf16():
     rng = np.random.default_rng(800)
     wl = _small(rng, 1, 48, 8, 2, 128, [100], "bf16", False, n_nodes=[37])
