@@ -73,6 +73,21 @@ def build_tree_mask(parent, n_nodes):
     return dict(bitmask=bitmask, dense=dense, depth=depth, status=status)
 
 
+def tensorize_tree(parent, n_nodes, prefix_len, L_max: int, W: int):
+    """depth, position ids, root-to-leaf paths (retrieve [B,L_max,W], -1 padded), path counts, status."""
+    parent, n_nodes, prefix_len = _i32(parent), _i32(n_nodes), _i32(prefix_len)
+    B, T = parent.shape
+    depth = np.zeros((B, T), dtype=np.int32)
+    pos = np.zeros((B, T), dtype=np.int32)
+    retrieve = np.zeros((B, L_max, W), dtype=np.int32)
+    n_paths = np.zeros(B, dtype=np.int32)
+    status = np.zeros(B, dtype=np.int32)
+    rc = lib().orc_tensorize_tree(_p(parent), _p(n_nodes), _p(prefix_len), B, T, L_max, W, _p(depth), _p(pos),
+                                  _p(retrieve), _p(n_paths), _p(status))
+    assert rc == 0, rc
+    return dict(depth=depth, position_ids=pos, retrieve=retrieve, n_paths=n_paths, status=status)
+
+
 def tree_verify_attention(q, k_cache, v_cache, prefix_len, kt, vt, dense, n_nodes, *, dtype: str,
                           block_table=None, scale: float = 0.0, want_lse: bool = True):
     """q [B,T,Hq,d]; kt/vt [B,T,Hkv,d]; cache contiguous [B,P_cap,Hkv,d] or paged [nb,Hkv,bs,d]."""

@@ -15,8 +15,10 @@
  * something other than itself - brute-force ancestor walks, closed forms,
  * numpy/torch float64 library attention on the special cases that reduce to it
  * (one-node tree = decode attention, chain = causal attention, per-node
- * sequential equivalence), a hand-worked 7-node example, and sequential-append
- * commit.  No function here is "parity unpinned".
+ * sequential equivalence), a hand-worked 7-node example, sequential-append
+ * commit, and for the path table parent walks from every leaf plus the closed
+ * forms of a chain, a star and a complete binary tree.  No function here is
+ * "parity unpinned".
  *
  * Conventions (shared with the seeded generators):
  *   node rows 0..n_nodes[b]-1 of sequence b are valid, row 0 is the root (the
@@ -138,6 +140,111 @@ int orc_build_tree_mask(const int32_t *parent, const int32_t *n_nodes, int B, in
     free(ep);
     free(dep);
     free(A);
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------
+ * Tree tensorization.  Section 3.2: node linearization with the dummy-root row
+ * 0, the ancestor table A[0][k] = k, A[l+1][k] = parent(A[l][k]), padding with
+ * device-defined values guarded by `valid`, and the structural invariants;
+ * Section 3.3 "Execution view": node k sits at position t + depth[k] behind an
+ * accepted prefix of length t.
+ *
+ * From parent[b][:] alone this writes, per sequence,
+ *   depth[k]         steps from k to row 0 (0 for padding),
+ *   position_ids[k]  prefix_len[b] + depth[k] (prefix_len[b] for padding),
+ *   retrieve[r][i]   one row per leaf, leaves in ascending row index; entry i is
+ *                    the node at depth i of the root-to-leaf path, read off the
+ *                    ancestor table as A[depth[leaf] - i][leaf]; -1 beyond the
+ *                    leaf and in rows beyond the last leaf,
+ *   n_paths          number of rows written.
+ * A leaf is a valid node that no valid node names as its parent (the root of a
+ * one-node tree is a leaf).  Nodes that break an invariant are first re-attached
+ * to the root exactly as orc_build_tree_mask does, so the two agree on the tree.
+ * More leaves than L_max: PATHS bit, the first L_max leaves are kept.  A path
+ * longer than W nodes: DEPTH bit, its first W nodes are kept.
+ * ---------------------------------------------------------------------- */
+#define ORC_TREE_PATHS 8  /* more leaves than rows in retrieve                         */
+#define ORC_TREE_DEPTH 16 /* a root-to-leaf path has more than W nodes                 */
+
+int orc_tensorize_tree(const int32_t *parent, const int32_t *n_nodes, const int32_t *prefix_len, int B, int T_max,
+                       int L_max, int W, int32_t *depth, int32_t *position_ids, int32_t *retrieve, int32_t *n_paths,
+                       int32_t *status) {
+    if (B < 0 || T_max < 1 || L_max < 1 || W < 1) return ORC_ERR_ARG;
+    int32_t *ep = (int32_t *)malloc(sizeof(int32_t) * (size_t)T_max);
+    int32_t *dep = (int32_t *)malloc(sizeof(int32_t) * (size_t)T_max);
+    int32_t *A = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T_max + 1) * (size_t)T_max);
+    uint8_t *has_child = (uint8_t *)malloc((size_t)T_max);
+    if (!ep || !dep || !A || !has_child) return ORC_ERR_NOMEM;
+    for (int b = 0; b < B; b++) {
+        int n = n_nodes[b];
+        if (n < 0) n = 0;
+        if (n > T_max) n = T_max;
+        const int32_t *par = parent + (size_t)b * T_max;
+        int32_t st = 0;
+        for (int k = 0; k < n; k++) {
+            int32_t p = par[k];
+            if (k == 0) {
+                if (p != 0) st |= ORC_TREE_RANGE;
+                ep[0] = 0;
+            } else if (p < 0 || p >= T_max) {
+                st |= ORC_TREE_RANGE;
+                ep[k] = 0;
+            } else if (p >= n) {
+                st |= ORC_TREE_CLOSURE;
+                ep[k] = 0;
+            } else {
+                ep[k] = p;
+            }
+        }
+        for (int k = 0; k < n; k++) {
+            int cur = k, steps = 0;
+            while (cur != 0 && steps < n) {
+                cur = ep[cur];
+                steps++;
+            }
+            dep[k] = (cur == 0) ? steps : -1;
+        }
+        for (int k = 0; k < n; k++)
+            if (dep[k] < 0) {
+                st |= ORC_TREE_CYCLE;
+                ep[k] = 0;
+                dep[k] = 1;
+            }
+        int Dmax = 0;
+        for (int k = 0; k < n; k++)
+            if (dep[k] > Dmax) Dmax = dep[k];
+        for (int k = 0; k < n; k++) A[k] = k;
+        for (int l = 0; l < Dmax; l++)
+            for (int k = 0; k < n; k++) A[(size_t)(l + 1) * T_max + k] = ep[A[(size_t)l * T_max + k]];
+        int P = prefix_len ? prefix_len[b] : 0;
+        if (P < 0) P = 0;
+        for (int k = 0; k < T_max; k++) {
+            if (depth) depth[(size_t)b * T_max + k] = (k < n) ? dep[k] : 0;
+            if (position_ids) position_ids[(size_t)b * T_max + k] = P + ((k < n) ? dep[k] : 0);
+        }
+        memset(has_child, 0, (size_t)T_max);
+        for (int k = 1; k < n; k++) has_child[ep[k]] = 1;
+        int32_t *rows = retrieve + (size_t)b * L_max * W;
+        for (size_t e = 0; e < (size_t)L_max * W; e++) rows[e] = -1;
+        int r = 0;
+        for (int k = 0; k < n; k++) {
+            if (has_child[k]) continue;
+            if (r >= L_max) {
+                st |= ORC_TREE_PATHS;
+                break;
+            }
+            if (dep[k] + 1 > W) st |= ORC_TREE_DEPTH;
+            for (int i = 0; i <= dep[k] && i < W; i++) rows[(size_t)r * W + i] = A[(size_t)(dep[k] - i) * T_max + k];
+            r++;
+        }
+        if (n_paths) n_paths[b] = r;
+        if (status) status[b] = st;
+    }
+    free(ep);
+    free(dep);
+    free(A);
+    free(has_child);
     return ORC_OK;
 }
 
