@@ -102,9 +102,18 @@ class Step:
         i32 = dict(dtype=torch.int32, device=dev)
         words = (T + 63) // 64
         L_max, W = wl.retrieve.shape[1], wl.W
+        # the tree tensors of a step are built on the device from `parent` (mask, depth, position ids, path table);
+        # the host-built path table of the workload is only used to check the device one once, before timing
+        self.L_max, self.W = L_max, W
         self.mask_out = dict(bitmask=torch.empty((B, T, words), dtype=torch.int64, device=dev),
                              dense=torch.empty((B, 1, T, T), dtype=torch.uint8, device=dev),
-                             depth=torch.empty((B, T), **i32), status=torch.empty((B,), **i32))
+                             depth=torch.empty((B, T), **i32), status=torch.empty((B,), **i32),
+                             position_ids=torch.empty((B, T), **i32), retrieve=torch.empty((B, L_max, W), **i32),
+                             n_paths=torch.empty((B,), **i32))
+        api.tensorize_tree(self.parent, self.n_nodes, self.prefix_len, L_max, W, out=self.mask_out)
+        torch.cuda.synchronize()
+        assert torch.equal(self.mask_out["retrieve"], self.retrieve), "device path table differs from the workload's"
+        self.retrieve = self.mask_out["retrieve"]
         self.out = torch.empty((layers, B, T, Hq, d), dtype=bf, device=dev)
         self.desc = api.attn_desc(self.q[0], self.kt[0], self.kc[0][0], self.block_table, self.P_max, 0.0, kv_split, attn_flags)
         self.ws = torch.empty((max(256, api.tree_verify_attention_workspace_bytes(self.desc)),), dtype=torch.uint8,
@@ -131,7 +140,7 @@ class Step:
 
     def run(self, s):
         api = self.api
-        api.build_tree_mask(self.parent, self.n_nodes, out=self.mask_out)
+        api.tensorize_tree(self.parent, self.n_nodes, self.prefix_len, self.L_max, self.W, out=self.mask_out)
         self.attention_layers(s)
         api.safe_gather_paths(self.retrieve, self.n_nodes, self.wl.T_max, 0, self.tokens3, out=self.gather_out)
         api.evaluate_posterior(self.logits, self.tokens, self.retrieve, self.n_nodes, 0, workspace=self.post_ws,
@@ -174,7 +183,7 @@ def cpu_baseline(wl_name, layers):
     import oracle
     from paper_2603_08088_amd import synth
     if wl_name == "c2":
-        wl, att_layers, note = synth.config2(), layers, f"one full step of config 2: mask + {layers} attention layers + gather + posterior + commit over {layers} layers"
+        wl, att_layers, note = synth.config2(), layers, f"one full step of config 2: mask + tree tensorization + {layers} attention layers + gather + posterior + commit over {layers} layers"
     else:
         wl, _ = make_host_workload(wl_name)
         return None
@@ -183,6 +192,8 @@ def cpu_baseline(wl_name, layers):
     vc = np.broadcast_to(wl.v_cache, (layers,) + wl.v_cache.shape).copy()
     t0 = time.perf_counter()
     m = oracle.build_tree_mask(wl.parent, wl.n_nodes)
+    tz = oracle.tensorize_tree(wl.parent, wl.n_nodes, wl.prefix_len, wl.retrieve.shape[1], wl.W)
+    assert np.array_equal(tz["retrieve"], wl.retrieve)
     for _ in range(att_layers):
         oracle.tree_verify_attention(wl.q, wl.k_cache, wl.v_cache, wl.prefix_len, wl.kt, wl.vt, m["dense"],
                                      wl.n_nodes, dtype=wl.dtype, block_table=wl.block_table, want_lse=False)

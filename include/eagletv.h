@@ -54,6 +54,8 @@ extern "C" {
 #define ETV_TREE_RANGE 1   /* parent[k] outside [0, T_max), or parent[0] != 0                   */
 #define ETV_TREE_CYCLE 2   /* repeated parent application from k does not reach row 0           */
 #define ETV_TREE_CLOSURE 4 /* valid node whose parent slot is padding (>= n_nodes)              */
+#define ETV_TREE_PATHS 8   /* etv_tensorize_tree: more leaves than rows in the path table        */
+#define ETV_TREE_DEPTH 16  /* etv_tensorize_tree: a root-to-leaf path has more than W nodes      */
 
 /* status bits written by etv_commit_accepted_kv */
 #define ETV_COMMIT_CAPACITY 1  /* prefix_len + accept_len + 1 exceeds capacity[b] (or the block table) */
@@ -96,6 +98,35 @@ ETV_API int32_t etv_hbm_read_probe(const void *buf, size_t bytes, void *sink, vo
  * ------------------------------------------------------------------------- */
 ETV_API int32_t etv_build_tree_mask(const int32_t *parent, const int32_t *n_nodes, int32_t B, int32_t T_max,
                             uint64_t *bitmask, uint8_t *dense, int32_t *depth, int32_t *status, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * tensorize_tree -- Section 3.2 ("Node linearization and base arrays", "Dummy-root
+ * indexing", "Ancestor tables", "Padding and batch semantics", "Structural
+ * invariants") and Section 3.3 ("Execution view": node k sits at position
+ * prefix length + depth[k]).
+ *
+ * Everything the verification step needs to know about the tree, from the parent
+ * array alone and in one launch: the outputs of etv_build_tree_mask plus position
+ * ids and the table of root-to-leaf paths (the retrieve indices that
+ * etv_safe_gather_paths and etv_evaluate_posterior consume).  One row per leaf,
+ * leaves in ascending row order; entry i of a row is the path's node at depth i;
+ * -1 behind the leaf and in the rows behind the last leaf.  A leaf is a valid node
+ * that no valid node names as its parent.  Nodes that break an invariant hang off
+ * the root, as in etv_build_tree_mask.
+ *
+ *  parent, n_nodes, bitmask, dense, depth, status   as for etv_build_tree_mask;
+ *                status may also carry ETV_TREE_PATHS (more than L_max leaves: the
+ *                first L_max are kept) and ETV_TREE_DEPTH (a path of more than W
+ *                nodes: its first W are kept)
+ *  prefix_len    in  int32 [B]              needed if position_ids is given; negative counts as 0
+ *  position_ids  out int32 [B, T_max]       prefix_len[b] + depth (prefix_len[b] for padding)  nullable
+ *  retrieve      out int32 [B, L_max, W]
+ *  n_paths       out int32 [B]              rows written per sequence                           nullable
+ * Requires 1 <= T_max <= ETV_MAX_TREE, L_max >= 1, W >= 1, L_max * W <= 2^24.
+ * ------------------------------------------------------------------------- */
+ETV_API int32_t etv_tensorize_tree(const int32_t *parent, const int32_t *n_nodes, const int32_t *prefix_len, int32_t B,
+                           int32_t T_max, int32_t L_max, int32_t W, uint64_t *bitmask, uint8_t *dense, int32_t *depth,
+                           int32_t *position_ids, int32_t *retrieve, int32_t *n_paths, int32_t *status, void *stream);
 
 /* ---------------------------------------------------------------------------
  * tree_verify_attention - Section 3.3 "Execution view" and "Tree attention mask".

@@ -29,6 +29,7 @@ ATTN_FLAG_KEY_HALVES = 8
 MAX_TREE, ATTN_MAX_TREE = 256, 128
 
 EXPORTS = ("etv_status_string", "etv_version", "etv_last_hip_error", "etv_hbm_read_probe", "etv_build_tree_mask",
+           "etv_tensorize_tree",
            "etv_tree_verify_attention_workspace_bytes", "etv_tree_verify_attention", "etv_safe_gather_paths",
            "etv_evaluate_posterior_workspace_bytes", "etv_evaluate_posterior", "etv_commit_accepted_kv")
 
@@ -69,6 +70,8 @@ def lib():
         l.etv_hbm_read_probe.argtypes = [vp, sz, vp, vp]
         l.etv_build_tree_mask.restype = i32
         l.etv_build_tree_mask.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp]
+        l.etv_tensorize_tree.restype = i32
+        l.etv_tensorize_tree.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         l.etv_tree_verify_attention_workspace_bytes.restype = sz
         l.etv_tree_verify_attention_workspace_bytes.argtypes = [C.POINTER(AttnDesc)]
         l.etv_tree_verify_attention.restype = i32
@@ -136,6 +139,31 @@ def build_tree_mask(parent: torch.Tensor, n_nodes: torch.Tensor, *, want_dense: 
                                    _ptr(status), _stream())
     _check("etv_build_tree_mask", rc)
     return dict(bitmask=bitmask, dense=dense, depth=depth, status=status)
+
+
+def tensorize_tree(parent: torch.Tensor, n_nodes: torch.Tensor, prefix_len: torch.Tensor, L_max: int, W: int, *,
+                   want_dense: bool = True, out: Optional[Dict[str, torch.Tensor]] = None):
+    """parent int32 [B,T_max], n_nodes, prefix_len int32 [B] -> the outputs of build_tree_mask plus position_ids
+    int32 [B,T_max], retrieve int32 [B,L_max,W] (root-to-leaf paths, -1 padded) and n_paths int32 [B]."""
+    B, T = parent.shape
+    dev = parent.device
+    words = (T + 63) // 64
+    o = out or {}
+    i32 = dict(dtype=torch.int32, device=dev)
+
+    def get(name, shape, dtype=torch.int32):
+        t = o.get(name)
+        return t if t is not None else torch.empty(shape, dtype=dtype, device=dev)
+    bitmask = get("bitmask", (B, T, words), torch.int64)
+    dense = o.get("dense") if out else (torch.empty((B, 1, T, T), dtype=torch.uint8, device=dev) if want_dense else None)
+    depth, pos = get("depth", (B, T)), get("position_ids", (B, T))
+    retrieve, n_paths, status = get("retrieve", (B, L_max, W)), get("n_paths", (B,)), get("status", (B,))
+    rc = lib().etv_tensorize_tree(_ptr(parent), _ptr(n_nodes), _ptr(prefix_len), B, T, L_max, W, _ptr(bitmask),
+                                  _ptr(dense), _ptr(depth), _ptr(pos), _ptr(retrieve), _ptr(n_paths), _ptr(status),
+                                  _stream())
+    _check("etv_tensorize_tree", rc)
+    return dict(bitmask=bitmask, dense=dense, depth=depth, position_ids=pos, retrieve=retrieve, n_paths=n_paths,
+                status=status)
 
 
 def attn_desc(q: torch.Tensor, kt: torch.Tensor, k_cache: Optional[torch.Tensor], block_table: Optional[torch.Tensor],

@@ -1,4 +1,4 @@
-"""GPU parity (bit-exact) for build_tree_mask, safe_gather_paths, evaluate_posterior, commit_accepted_kv."""
+"""GPU parity (bit-exact) for build_tree_mask, tensorize_tree, safe_gather_paths, evaluate_posterior, commit_accepted_kv."""
 import numpy as np
 import pytest
 import torch
@@ -34,6 +34,70 @@ def test_mask_random_trees(T):
         par[b, n[b]:] = rng.integers(-5, T + 5, size=T - n[b])   # garbage in padding
     ref = _mask_case(par, n)
     assert np.all(ref["status"] == 0)
+
+
+def _tensorize_case(parents_np, n_np, P_np, L_max, W):
+    ref = oracle.tensorize_tree(parents_np, n_np, P_np, L_max, W)
+    refm = oracle.build_tree_mask(parents_np, n_np)
+    got = api.tensorize_tree(to_dev(parents_np.astype(np.int32)), to_dev(np.asarray(n_np, dtype=np.int32)),
+                             to_dev(np.asarray(P_np, dtype=np.int32)), L_max, W)
+    torch.cuda.synchronize()
+    for name in ("depth", "position_ids", "retrieve", "n_paths", "status"):
+        assert np.array_equal(bits_of(got[name]), ref[name]), name
+    assert np.array_equal(bits_of(got["bitmask"]).view(np.uint64), refm["bitmask"])
+    assert np.array_equal(bits_of(got["dense"]), refm["dense"])
+    return ref
+
+
+@pytest.mark.parametrize("T", [1, 2, 7, 15, 60, 64, 65, 127, 128, 200, 256])
+def test_tensorize_random_trees(T):
+    rng = np.random.default_rng(2000 + T)
+    B = 9
+    par = np.zeros((B, T), dtype=np.int32)
+    n = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        n[b] = T if b < 3 else rng.integers(0, T + 1)
+        par[b, : n[b]] = random_tree(rng, max(1, int(n[b])))[: n[b]]
+        par[b, n[b]:] = rng.integers(-5, T + 5, size=T - n[b])   # garbage in padding
+    P = rng.integers(-3, 100000, size=B)
+    ref = _tensorize_case(par, n, P, T, T)                        # room for every leaf and every depth
+    assert np.all(ref["status"] == 0)
+    _tensorize_case(par, n, P, max(1, T // 3), max(1, T // 4))   # overflow of both kinds on most sequences
+    _tensorize_case(par, n, P, 1, 1)
+
+
+def test_tensorize_shapes_of_the_workloads_invalid_trees_and_worked_example():
+    ex = golden("worked_example.json")
+    ref = _tensorize_case(np.asarray([ex["parent"]], dtype=np.int32), [7], [100], 4, 4)
+    assert ref["retrieve"][0, :3].tolist() == ex["retrieve"]
+    # chain, star, and the generators of the paper-shaped workloads: the device table equals the host-built one
+    for par, W in ((synth.tree_chain(128), 128), (synth.tree_star(128), 2),
+                   (synth.tree_eagle(np.random.default_rng(3), 60, 6, 10), 7),
+                   (synth.tree_bfs(np.random.default_rng(4), 128, 8, 4), 9),
+                   (synth.tree_spine_leaves(64, 8, 4), 9)):
+        T = len(par)
+        host = synth.build_retrieve(par, W)
+        ref = _tensorize_case(par[None].astype(np.int32), [T], [4096], host.shape[0] + 2, W)
+        assert ref["n_paths"][0] == host.shape[0] and ref["status"][0] == 0
+        assert np.array_equal(ref["retrieve"][0, :host.shape[0]], host)
+    rng = np.random.default_rng(6)
+    T, B = 40, 64
+    par = np.stack([random_tree(rng, T) for _ in range(B)])
+    n = np.full(B, T, dtype=np.int32)
+    for b in range(B):
+        kind = b % 4
+        k = int(rng.integers(1, T))
+        if kind == 0:
+            par[b, k] = rng.choice([-1, -7, T, T + 3, 2 ** 30])
+        elif kind == 1:
+            j = int(rng.integers(1, T))
+            par[b, k] = j; par[b, j] = k            # 2-cycle (or self loop when j == k)
+        elif kind == 2:
+            n[b] = T - 5; par[b, int(rng.integers(1, T - 5))] = T - 2   # parent in the padded region
+        else:
+            par[b, 0] = 3
+    ref = _tensorize_case(par, n, np.zeros(B), T, T)
+    assert np.all(ref["status"] != 0)
 
 
 def test_mask_invalid_trees_and_worked_example():

@@ -13,6 +13,9 @@ pytestmark = pytest.mark.gpu
 
 def _oracle_step(wl, kt, vt, kc, vc, q):
     m = oracle.build_tree_mask(wl.parent, wl.n_nodes)
+    m.update({k: v for k, v in oracle.tensorize_tree(wl.parent, wl.n_nodes, wl.prefix_len, wl.retrieve.shape[1],
+                                                     wl.W).items() if k not in m})
+    assert np.array_equal(m["retrieve"], wl.retrieve)   # the oracle's path table is the generator's
     outs = [oracle.tree_verify_attention(q[l], kc[l], vc[l], wl.prefix_len, kt[l], vt[l], m["dense"], wl.n_nodes,
                                          dtype=wl.dtype, block_table=wl.block_table, want_lse=False)[0]
             for l in range(q.shape[0])]
@@ -42,7 +45,9 @@ def test_full_step_config2_eager_and_graph(paged):
     i32 = dict(dtype=torch.int32, device="cuda")
     mask_out = dict(bitmask=torch.empty((B, T, 1), dtype=torch.int64, device="cuda"),
                     dense=torch.empty((B, 1, T, T), dtype=torch.uint8, device="cuda"),
-                    depth=torch.empty((B, T), **i32), status=torch.empty((B,), **i32))
+                    depth=torch.empty((B, T), **i32), status=torch.empty((B,), **i32),
+                    position_ids=torch.empty((B, T), **i32), n_paths=torch.empty((B,), **i32),
+                    retrieve=torch.empty((B,) + wl.retrieve.shape[1:], **i32))
     out = torch.empty_like(dq)
     desc = api.attn_desc(dq[0], dkt[0], to_dev(kc[0]), d.block_table, d.P_max)
     ws = torch.empty(max(256, api.tree_verify_attention_workspace_bytes(desc)), dtype=torch.uint8, device="cuda")
@@ -55,19 +60,22 @@ def test_full_step_config2_eager_and_graph(paged):
     cout = dict(prefix_len_out=torch.empty((B,), **i32), slot_map=torch.empty((B, W), **i32), status=torch.empty((B,), **i32))
 
     def step(dkc, dvc):
-        api.build_tree_mask(d.parent, d.n_nodes, out=mask_out)
+        # the tree tensors come from the device: the path table the later calls read is the one written here
+        api.tensorize_tree(d.parent, d.n_nodes, d.prefix_len, L_max, W, out=mask_out)
         for l in range(L):
             api.tree_verify_attention(dq[l], dkc[l], dvc[l], d.prefix_len, dkt[l], dvt[l], mask_out["bitmask"], d.n_nodes,
                                       P_max=d.P_max, block_table=d.block_table, out=out[l], want_lse=False,
                                       workspace=ws, desc=desc)
-        api.safe_gather_paths(d.retrieve, d.n_nodes, T, 0, d.tokens.reshape(B, T, 1), out=gout)
-        api.evaluate_posterior(d.logits, d.tokens, d.retrieve, d.n_nodes, 0, workspace=pws, out=pout)
+        api.safe_gather_paths(mask_out["retrieve"], d.n_nodes, T, 0, d.tokens.reshape(B, T, 1), out=gout)
+        api.evaluate_posterior(d.logits, d.tokens, mask_out["retrieve"], d.n_nodes, 0, workspace=pws, out=pout)
         api.commit_accepted_kv(dkt, dvt, dkc, dvc, d.prefix_len, d.capacity, d.n_nodes, pout["acc_nodes"],
                                pout["accept_len"], block_table=d.block_table, out=cout)
 
     def check(dkc, dvc, tag):
         torch.cuda.synchronize()
         assert np.array_equal(bits_of(mask_out["dense"]), rm["dense"]), tag
+        for key in ("depth", "position_ids", "retrieve", "n_paths", "status"):
+            assert np.array_equal(bits_of(mask_out[key]), rm[key]), (tag, key)
         for l in range(L):
             err, rel, pz = attention_errors(out[l], routs[l], wl.n_nodes)
             assert pz and err <= 2e-2 and rel <= 2e-2, (tag, l, err, rel)
@@ -94,7 +102,7 @@ def test_full_step_config2_eager_and_graph(paged):
     with torch.cuda.graph(g):
         step(dkc2, dvc2)
     for rep in range(3):
-        out.zero_(); pout["accept_len"].fill_(-7); cout["slot_map"].fill_(-7)
+        out.zero_(); pout["accept_len"].fill_(-7); cout["slot_map"].fill_(-7); mask_out["retrieve"].fill_(-7)
         dkc2.copy_(to_dev(kc)); dvc2.copy_(to_dev(vc))     # eager work between replays
         torch.cuda.synchronize()
         g.replay()
