@@ -142,13 +142,12 @@ class Step:
         api = self.api
         api.tensorize_tree(self.parent, self.n_nodes, self.prefix_len, self.L_max, self.W, out=self.mask_out)
         self.attention_layers(s)
-        api.safe_gather_paths(self.retrieve, self.n_nodes, self.wl.T_max, 0, self.tokens3, out=self.gather_out)
-        api.evaluate_posterior(self.logits, self.tokens, self.retrieve, self.n_nodes, 0, workspace=self.post_ws,
-                               out=self.post_out)
-        # the new prefix length goes to its own buffer so that every timed step sees the same prefix
-        api.commit_accepted_kv(self.kt, self.vt, self.kc[s], self.vc[s], self.prefix_len, self.capacity,
-                               self.n_nodes, self.post_out["acc_nodes"], self.post_out["accept_len"],
-                               block_table=self.block_table, out=self.commit_out)
+        # gather + acceptance + commit as the fused epilogue (three launches); the new prefix length goes to its
+        # own buffer so that every timed step sees the same prefix
+        api.verify_epilogue(self.logits, self.tokens, self.retrieve, self.n_nodes, self.kt, self.vt, self.kc[s],
+                            self.vc[s], self.prefix_len, self.capacity, block_table=self.block_table, dummy=0,
+                            src=self.tokens3, workspace=self.post_ws, gather_out=self.gather_out,
+                            post_out=self.post_out, commit_out=self.commit_out)
 
     def capture(self, fn):
         torch = self.torch

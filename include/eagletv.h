@@ -255,6 +255,28 @@ ETV_API int32_t etv_commit_accepted_kv(const etv_commit_desc *h_desc, const void
                                const int32_t *accept_len, int32_t *prefix_len_out, int32_t *slot_map,
                                int32_t *status, void *stream);
 
+/* ---------------------------------------------------------------------------
+ * verify_epilogue -- everything after the teacher forward in three launches
+ * instead of five: the safe gather (Section 3.2 "Dummy-root indexing"), greedy
+ * acceptance (Sections 2.3 and 5.1) and the commit of the accepted rows
+ * (Section 3.1 "Commit by path indices and prefix-sharing fast reorder"), with
+ * the accepted length and nodes staying on the device between them.  Arguments,
+ * layouts, outputs and status bits are those of etv_safe_gather_paths,
+ * etv_evaluate_posterior and etv_commit_accepted_kv called in that order with
+ * W = h_desc->W as the row length of retrieve, acc_nodes and slot_map; the
+ * results are identical.  safe, pvalid and (src, gathered) are nullable as there.
+ * workspace: etv_evaluate_posterior_workspace_bytes(B, T_max, V) bytes.
+ * Requires T_max <= ETV_MAX_TREE and W <= ETV_MAX_TREE.
+ * ------------------------------------------------------------------------- */
+ETV_API int32_t etv_verify_epilogue(const etv_commit_desc *h_desc, const float *logits, int32_t V, const int32_t *tokens,
+                            const int32_t *retrieve, int32_t L_max, int32_t dummy, const void *src, size_t row_bytes,
+                            int32_t *safe, uint8_t *pvalid, void *gathered, int32_t *argmax, int32_t *len,
+                            int32_t *best, int32_t *accept_len, int32_t *acc_nodes, int32_t *bonus, const void *kt,
+                            const void *vt, void *k_cache, void *v_cache, const int32_t *block_table,
+                            const int32_t *prefix_len, const int32_t *capacity, const int32_t *n_nodes,
+                            int32_t *prefix_len_out, int32_t *slot_map, int32_t *status, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,7 +31,8 @@ MAX_TREE, ATTN_MAX_TREE = 256, 128
 EXPORTS = ("etv_status_string", "etv_version", "etv_last_hip_error", "etv_hbm_read_probe", "etv_build_tree_mask",
            "etv_tensorize_tree",
            "etv_tree_verify_attention_workspace_bytes", "etv_tree_verify_attention", "etv_safe_gather_paths",
-           "etv_evaluate_posterior_workspace_bytes", "etv_evaluate_posterior", "etv_commit_accepted_kv")
+           "etv_evaluate_posterior_workspace_bytes", "etv_evaluate_posterior", "etv_commit_accepted_kv",
+           "etv_verify_epilogue")
 
 
 class AttnDesc(C.Structure):
@@ -78,6 +79,8 @@ def lib():
         l.etv_tree_verify_attention.argtypes = [C.POINTER(AttnDesc)] + [vp] * 12 + [sz, vp]
         l.etv_safe_gather_paths.restype = i32
         l.etv_safe_gather_paths.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, sz, vp, vp, vp, vp]
+        l.etv_verify_epilogue.restype = i32
+        l.etv_verify_epilogue.argtypes = [C.POINTER(CommitDesc), vp, i32, vp, vp, i32, i32, vp, sz] + [vp] * 21 + [sz, vp]
         l.etv_evaluate_posterior_workspace_bytes.restype = sz
         l.etv_evaluate_posterior_workspace_bytes.argtypes = [i32, i32, i32]
         l.etv_evaluate_posterior.restype = i32
@@ -254,6 +257,57 @@ def evaluate_posterior(logits, tokens, retrieve, n_nodes, dummy: int = 0, worksp
                                       _ptr(workspace), workspace.numel(), _stream())
     _check("etv_evaluate_posterior", rc)
     return dict(argmax=g, len=ln, best=best, accept_len=A, acc_nodes=acc, bonus=bonus)
+
+
+def _commit_desc(kt, k_cache, block_table, W: int) -> CommitDesc:
+    Lyr, B, T, Hkv, d = kt.shape
+    assert k_cache.shape[0] == Lyr
+    dsc = CommitDesc(B=B, T_max=T, Hkv=Hkv, d=d, elem_bytes=kt.element_size(), n_layers=Lyr, W=W, block_size=0,
+                     max_blocks=0, num_blocks=0, P_cap=0, reserved=0,
+                     cache_layer_stride=k_cache.stride(0) if Lyr > 1 else k_cache[0].numel())
+    if block_table is not None:
+        dsc.block_size, dsc.max_blocks, dsc.num_blocks = k_cache.shape[3], block_table.shape[1], k_cache.shape[1]
+    else:
+        dsc.P_cap = k_cache.shape[2]
+    return dsc
+
+
+def verify_epilogue(logits, tokens, retrieve, n_nodes, kt, vt, k_cache, v_cache, prefix_len, capacity, *,
+                    block_table=None, dummy: int = 0, src: Optional[torch.Tensor] = None, workspace=None,
+                    gather_out: Optional[Dict[str, torch.Tensor]] = None,
+                    post_out: Optional[Dict[str, torch.Tensor]] = None,
+                    commit_out: Optional[Dict[str, torch.Tensor]] = None):
+    """safe_gather_paths + evaluate_posterior + commit_accepted_kv in three launches; same tensors and results.
+    Returns (gather dict, posterior dict, commit dict)."""
+    B, T, V = logits.shape
+    _, L, W = retrieve.shape
+    dev = logits.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    go, po, co = gather_out or {}, post_out or {}, commit_out or {}
+
+    def get(d, name, shape, dtype=torch.int32):
+        t = d.get(name)
+        return t if t is not None else torch.empty(shape, dtype=dtype, device=dev)
+    safe, pvalid = get(go, "safe", (B, L, W)), get(go, "pvalid", (B, L, W), torch.uint8)
+    gathered, row_bytes = None, 0
+    if src is not None:
+        row_bytes = src[0, 0].numel() * src.element_size()
+        gathered = get(go, "gathered", (B, L, W) + tuple(src.shape[2:]), src.dtype)
+    g, ln, best = get(po, "argmax", (B, T)), get(po, "len", (B, L)), get(po, "best", (B,))
+    A, acc, bonus = get(po, "accept_len", (B,)), get(po, "acc_nodes", (B, W)), get(po, "bonus", (B,))
+    plo, slot, status = get(co, "prefix_len_out", (B,)), get(co, "slot_map", (B, W)), get(co, "status", (B,))
+    if workspace is None:
+        workspace = torch.empty((max(256, evaluate_posterior_workspace_bytes(B, T, V)),), dtype=torch.uint8, device=dev)
+    dsc = _commit_desc(kt, k_cache, block_table, W)
+    rc = lib().etv_verify_epilogue(C.byref(dsc), _ptr(logits), V, _ptr(tokens), _ptr(retrieve), L, dummy, _ptr(src),
+                                   row_bytes, _ptr(safe), _ptr(pvalid), _ptr(gathered), _ptr(g), _ptr(ln), _ptr(best),
+                                   _ptr(A), _ptr(acc), _ptr(bonus), _ptr(kt), _ptr(vt), _ptr(k_cache), _ptr(v_cache),
+                                   _ptr(block_table), _ptr(prefix_len), _ptr(capacity), _ptr(n_nodes), _ptr(plo),
+                                   _ptr(slot), _ptr(status), _ptr(workspace), workspace.numel(), _stream())
+    _check("etv_verify_epilogue", rc)
+    return (dict(safe=safe, pvalid=pvalid, gathered=gathered),
+            dict(argmax=g, len=ln, best=best, accept_len=A, acc_nodes=acc, bonus=bonus),
+            dict(prefix_len_out=plo, slot_map=slot, status=status))
 
 
 def commit_accepted_kv(kt, vt, k_cache, v_cache, prefix_len, capacity, n_nodes, acc_nodes, accept_len, *,

@@ -3,7 +3,7 @@
 // gathered from the step's tree K/V buffer and appended, for every layer in one launch.  Because
 // the tree K/V lives in its own buffer and not in the cache tail, source and destination never
 // overlap and every copy is independent.
-#include "etv_common.h"
+#include "epilogue_parts.h"
 
 namespace etv {
 
@@ -16,43 +16,8 @@ __global__ void commit_plan_kernel(etv_commit_desc dsc, const int32_t *__restric
                                    int32_t *__restrict__ slot_map, int32_t *__restrict__ status) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= dsc.B) return;
-    const int W = dsc.W;
-    const int P = prefix_len[b], A = accept_len[b];
-    const int n = clampi(n_nodes[b], 0, dsc.T_max);
-    int32_t st = 0;
-    if (A < 0 || A > W - 1) st |= ETV_COMMIT_BAD_LEN;
-    if (!st) {
-        for (int i = 0; i <= A; i++) {
-            int32_t nd = acc_nodes[(size_t)b * W + i];
-            if (nd < 0 || nd >= n) st |= ETV_COMMIT_BAD_NODE;
-        }
-        if ((long)P + A + 1 > (long)capacity[b] || P < 0) st |= ETV_COMMIT_CAPACITY;
-        if (!(st & ETV_COMMIT_CAPACITY) && dsc.block_size > 0) {
-            for (int i = 0; i <= A; i++) {
-                int lb = (P + i) / dsc.block_size;
-                if (lb >= dsc.max_blocks) {
-                    st |= ETV_COMMIT_CAPACITY;
-                    break;
-                }
-                int blk = block_table[(size_t)b * dsc.max_blocks + lb];
-                if (blk < 0 || blk >= dsc.num_blocks) st |= ETV_COMMIT_BAD_BLOCK;
-            }
-        } else if (!(st & ETV_COMMIT_CAPACITY) && (long)P + A + 1 > (long)dsc.P_cap) {
-            st |= ETV_COMMIT_CAPACITY;
-        }
-    }
-    for (int i = 0; i < W; i++) {
-        int32_t slot = -1;
-        if (!st && i <= A) {
-            int pos = P + i;
-            slot = dsc.block_size > 0 ? block_table[(size_t)b * dsc.max_blocks + pos / dsc.block_size] * dsc.block_size +
-                                            pos % dsc.block_size
-                                      : pos;
-        }
-        slot_map[(size_t)b * W + i] = slot;
-    }
-    status[b] = st;
-    prefix_len_out[b] = st ? P : P + A + 1;
+    commit_plan_for_sequence(dsc, b, block_table, prefix_len[b], capacity[b], clampi(n_nodes[b], 0, dsc.T_max),
+                             acc_nodes + (size_t)b * dsc.W, accept_len[b], prefix_len_out, slot_map, status);
 }
 
 // grid (W, B, n_layers), 256 threads: one appended position of one sequence in one layer.
@@ -91,14 +56,11 @@ __global__ void __launch_bounds__(256) commit_copy_kernel(etv_commit_desc dsc, c
 
 }  // namespace etv
 
-extern "C" int32_t etv_commit_accepted_kv(const etv_commit_desc *h, const void *kt, const void *vt, void *k_cache,
-                                          void *v_cache, const int32_t *block_table, const int32_t *prefix_len,
-                                          const int32_t *capacity, const int32_t *n_nodes, const int32_t *acc_nodes,
-                                          const int32_t *accept_len, int32_t *prefix_len_out, int32_t *slot_map,
-                                          int32_t *status, void *stream) {
-    if (!h || !kt || !vt || !k_cache || !v_cache || !prefix_len || !capacity || !n_nodes || !acc_nodes ||
-        !accept_len || !prefix_len_out || !slot_map || !status)
-        return ETV_ERR_INVALID_ARG;
+namespace etv {
+
+int32_t check_commit_args(const etv_commit_desc *h, const void *kt, const void *vt, const void *k_cache,
+                          const void *v_cache, const int32_t *block_table) {
+    if (!h || !kt || !vt || !k_cache || !v_cache) return ETV_ERR_INVALID_ARG;
     if (h->B < 0 || h->T_max < 1 || h->Hkv < 1 || h->d < 1 || h->n_layers < 1 || h->W < 1) return ETV_ERR_INVALID_ARG;
     if (h->elem_bytes != 2 && h->elem_bytes != 4) return ETV_ERR_UNSUPPORTED;
     if (((size_t)h->d * h->elem_bytes) % 16 != 0) return ETV_ERR_UNSUPPORTED;
@@ -107,15 +69,34 @@ extern "C" int32_t etv_commit_accepted_kv(const etv_commit_desc *h, const void *
     if (h->block_size == 0 && h->P_cap < 1) return ETV_ERR_INVALID_ARG;
     if (((uintptr_t)kt | (uintptr_t)vt | (uintptr_t)k_cache | (uintptr_t)v_cache) & 15) return ETV_ERR_INVALID_ARG;
     if (((size_t)h->cache_layer_stride * h->elem_bytes) % 16 != 0) return ETV_ERR_INVALID_ARG;
-    if (h->B == 0) return ETV_OK;
     if (h->B > 65535 || h->n_layers > 65535) return ETV_ERR_UNSUPPORTED;
+    return ETV_OK;
+}
+
+int32_t launch_commit_copy(const etv_commit_desc *h, const void *kt, const void *vt, void *k_cache, void *v_cache,
+                           const int32_t *acc_nodes, const int32_t *slot_map, hipStream_t s) {
+    hipLaunchKernelGGL(commit_copy_kernel, dim3(h->W, h->B, h->n_layers), dim3(256), 0, s, *h,
+                       static_cast<const uint8_t *>(kt), static_cast<const uint8_t *>(vt),
+                       static_cast<uint8_t *>(k_cache), static_cast<uint8_t *>(v_cache), acc_nodes, slot_map);
+    return check_launch();
+}
+
+}  // namespace etv
+
+extern "C" int32_t etv_commit_accepted_kv(const etv_commit_desc *h, const void *kt, const void *vt, void *k_cache,
+                                          void *v_cache, const int32_t *block_table, const int32_t *prefix_len,
+                                          const int32_t *capacity, const int32_t *n_nodes, const int32_t *acc_nodes,
+                                          const int32_t *accept_len, int32_t *prefix_len_out, int32_t *slot_map,
+                                          int32_t *status, void *stream) {
+    if (!prefix_len || !capacity || !n_nodes || !acc_nodes || !accept_len || !prefix_len_out || !slot_map || !status)
+        return ETV_ERR_INVALID_ARG;
+    int32_t rc = etv::check_commit_args(h, kt, vt, k_cache, v_cache, block_table);
+    if (rc != ETV_OK) return rc;
+    if (h->B == 0) return ETV_OK;
     hipStream_t s = etv::as_stream(stream);
     hipLaunchKernelGGL(etv::commit_plan_kernel, dim3((h->B + 63) / 64), dim3(64), 0, s, *h, block_table, prefix_len,
                        capacity, n_nodes, acc_nodes, accept_len, prefix_len_out, slot_map, status);
-    int32_t rc = etv::check_launch();
+    rc = etv::check_launch();
     if (rc != ETV_OK) return rc;
-    hipLaunchKernelGGL(etv::commit_copy_kernel, dim3(h->W, h->B, h->n_layers), dim3(256), 0, s, *h,
-                       static_cast<const uint8_t *>(kt), static_cast<const uint8_t *>(vt),
-                       static_cast<uint8_t *>(k_cache), static_cast<uint8_t *>(v_cache), acc_nodes, slot_map);
-    return etv::check_launch();
+    return etv::launch_commit_copy(h, kt, vt, k_cache, v_cache, acc_nodes, slot_map, s);
 }

@@ -273,3 +273,47 @@ def test_hbm_read_probe_runs_and_rejects_bad_arguments():
         api.hbm_read_probe(buf[: 2 ** 16], sink)   # below the 1 MiB minimum
     with pytest.raises(api.EtvError):
         api.hbm_read_probe(buf[1:], sink)          # misaligned
+
+
+def _epilogue_case(wl, L=2, dummy=0, spoil=None):
+    """The fused epilogue against the oracle's gather, acceptance and commit (and so against the separate calls)."""
+    rng = np.random.default_rng(77)
+    kt = np.stack([wl.kt] + [synth._values(rng, wl.kt.shape, wl.dtype) for _ in range(L - 1)])
+    vt = np.stack([wl.vt] + [synth._values(rng, wl.vt.shape, wl.dtype) for _ in range(L - 1)])
+    kc = np.stack([wl.k_cache] + [synth._values(rng, wl.k_cache.shape, wl.dtype) for _ in range(L - 1)])
+    vc = np.stack([wl.v_cache] + [synth._values(rng, wl.v_cache.shape, wl.dtype) for _ in range(L - 1)])
+    capacity = wl.capacity.copy()
+    if spoil is not None:
+        capacity[spoil] = wl.prefix_len[spoil]          # no room: that sequence must be left untouched
+    tok3 = wl.tokens.reshape(wl.B, wl.T_max, 1)
+    rg = oracle.safe_gather_paths(wl.retrieve, wl.n_nodes, wl.T_max, dummy, tok3)
+    rp = oracle.evaluate_posterior(wl.logits, wl.tokens, wl.retrieve, wl.n_nodes, dummy)
+    okc, ovc = kc.copy(), vc.copy()
+    rc = oracle.commit_accepted_kv(kt, vt, okc, ovc, wl.prefix_len, capacity, wl.n_nodes, rp["acc_nodes"],
+                                   rp["accept_len"], block_table=wl.block_table)
+    d = DevWorkload(wl)
+    dkc, dvc = to_dev(kc), to_dev(vc)
+    g, p, c = api.verify_epilogue(d.logits, d.tokens, d.retrieve, d.n_nodes, to_dev(kt), to_dev(vt), dkc, dvc,
+                                  d.prefix_len, to_dev(capacity), block_table=d.block_table, dummy=dummy,
+                                  src=d.tokens.reshape(wl.B, wl.T_max, 1))
+    torch.cuda.synchronize()
+    for key in ("safe", "pvalid", "gathered"):
+        assert np.array_equal(bits_of(g[key]), rg[key]), key
+    for key in rp:
+        assert np.array_equal(bits_of(p[key]), rp[key]), key
+    for key in rc:
+        assert np.array_equal(bits_of(c[key]), rc[key]), key
+    assert np.array_equal(bits_of(dkc), okc) and np.array_equal(bits_of(dvc), ovc)
+    return rp, rc
+
+
+def test_fused_epilogue_matches_gather_acceptance_and_commit():
+    rp, rc = _epilogue_case(synth.config1())
+    assert np.all(rc["status"] == 0)
+    for paged in (False, True):
+        rp, rc = _epilogue_case(synth.config2(paged=paged, P=300))
+        assert np.all(rc["status"] == 0)
+    rp, rc = _epilogue_case(synth.config3(B=4, lo=100, hi=600), spoil=2)     # ragged, paged, one sequence out of room
+    assert rc["status"][2] != 0 and np.all(np.delete(rc["status"], 2) == 0)
+    assert len(set(rp["accept_len"].tolist())) > 1
+    _epilogue_case(synth.config5(16, 4, B=6, P=200), dummy=3)               # padding-heavy path table, dummy != 0

@@ -27,8 +27,8 @@ def _oracle_step(wl, kt, vt, kc, vc, q):
     return m, outs, g, p, c, kc2, vc2
 
 
-@pytest.mark.parametrize("paged", [False, True])
-def test_full_step_config2_eager_and_graph(paged):
+@pytest.mark.parametrize("paged,fused", [(False, False), (True, False), (False, True), (True, True)])
+def test_full_step_config2_eager_and_graph(paged, fused):
     L = 3
     wl = synth.config2(paged=paged)
     rng = np.random.default_rng(99)
@@ -66,6 +66,11 @@ def test_full_step_config2_eager_and_graph(paged):
             api.tree_verify_attention(dq[l], dkc[l], dvc[l], d.prefix_len, dkt[l], dvt[l], mask_out["bitmask"], d.n_nodes,
                                       P_max=d.P_max, block_table=d.block_table, out=out[l], want_lse=False,
                                       workspace=ws, desc=desc)
+        if fused:   # gather + acceptance + commit through the fused epilogue entry point
+            api.verify_epilogue(d.logits, d.tokens, mask_out["retrieve"], d.n_nodes, dkt, dvt, dkc, dvc, d.prefix_len,
+                                d.capacity, block_table=d.block_table, dummy=0, src=d.tokens.reshape(B, T, 1),
+                                workspace=pws, gather_out=gout, post_out=pout, commit_out=cout)
+            return
         api.safe_gather_paths(mask_out["retrieve"], d.n_nodes, T, 0, d.tokens.reshape(B, T, 1), out=gout)
         api.evaluate_posterior(d.logits, d.tokens, mask_out["retrieve"], d.n_nodes, 0, workspace=pws, out=pout)
         api.commit_accepted_kv(dkt, dvt, dkc, dvc, d.prefix_len, d.capacity, d.n_nodes, pout["acc_nodes"],
