@@ -88,6 +88,22 @@ def tensorize_tree(parent, n_nodes, prefix_len, L_max: int, W: int):
     return dict(depth=depth, position_ids=pos, retrieve=retrieve, n_paths=n_paths, status=status)
 
 
+def lm_head_argmax(hidden, weight, n_nodes, *, dtype: str, want_logits: bool = False):
+    """hidden [B,T,D], weight [V,D] -> argmax int32 [B,T] (lowest index on ties, -1 for padding), max logit
+    float64 [B,T], and the fp64 logits [B,T,V] on request."""
+    B, T, D = hidden.shape
+    V = weight.shape[0]
+    argmax = np.zeros((B, T), dtype=np.int32)
+    maxval = np.zeros((B, T), dtype=np.float64)
+    logits = np.zeros((B, T, V), dtype=np.float64) if want_logits else None
+    f = lib().orc_lm_head_argmax
+    f.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p] + [C.c_int] * 4 + [C.c_void_p] * 3
+    rc = f(_p(np.ascontiguousarray(hidden)), _p(np.ascontiguousarray(weight)), _dt(dtype), _p(_i32(n_nodes)), B, T, D,
+           V, _p(argmax), _p(maxval), _p(logits))
+    assert rc == 0, rc
+    return dict(argmax=argmax, maxval=maxval, logits=logits)
+
+
 def tree_verify_attention(q, k_cache, v_cache, prefix_len, kt, vt, dense, n_nodes, *, dtype: str,
                           block_table=None, scale: float = 0.0, want_lse: bool = True):
     """q [B,T,Hq,d]; kt/vt [B,T,Hkv,d]; cache contiguous [B,P_cap,Hkv,d] or paged [nb,Hkv,bs,d]."""

@@ -558,3 +558,47 @@ int orc_num_threads(void) {
 #endif
     return n;
 }
+
+/* ------------------------------------------------------------------------
+ * Teacher head + greedy choice.  Section 3.3 "Execution view" / "Mapping
+ * teacher outputs to node verification scores": the teacher turns the hidden
+ * state of node k into logits l[k] over the vocabulary; Section 5.1: greedy
+ * decoding takes the argmax.  Plain definition: logits[r][v] = sum_c
+ * hidden[r][c] * weight[v][c] in fp64 from the exact input values, argmax over
+ * v with the lowest index on ties.  Rows of padded nodes give argmax -1.
+ *   hidden [B, T_max, D], weight [V, D] (dtype 0 = f32, 1 = bf16 bit patterns)
+ *   argmax int32 [B, T_max]; maxval double [B, T_max] (nullable);
+ *   logits double [B, T_max, V] (nullable: only for small cases)
+ * ---------------------------------------------------------------------- */
+int orc_lm_head_argmax(const void *hidden, const void *weight, int dtype, const int32_t *n_nodes, int B, int T_max,
+                       int D, int V, int32_t *argmax, double *maxval, double *logits) {
+    if (B < 0 || T_max < 1 || D < 1 || V < 1) return ORC_ERR_ARG;
+#pragma omp parallel for schedule(dynamic)
+    for (int r = 0; r < B * T_max; r++) {
+        int b = r / T_max, k = r % T_max;
+        int n = n_nodes[b];
+        if (n < 0) n = 0;
+        if (n > T_max) n = T_max;
+        if (k >= n) {
+            argmax[r] = -1;
+            if (maxval) maxval[r] = -INFINITY;
+            if (logits)
+                for (int v = 0; v < V; v++) logits[(size_t)r * V + v] = 0.0;
+            continue;
+        }
+        double best = -INFINITY;
+        int bi = -1;
+        for (int v = 0; v < V; v++) {
+            double acc = 0.0;
+            for (int c = 0; c < D; c++) acc += load_val(hidden, dtype, (size_t)r * D + c) * load_val(weight, dtype, (size_t)v * D + c);
+            if (logits) logits[(size_t)r * V + v] = acc;
+            if (acc > best) {
+                best = acc;
+                bi = v;
+            }
+        }
+        argmax[r] = bi;
+        if (maxval) maxval[r] = best;
+    }
+    return ORC_OK;
+}
