@@ -38,6 +38,7 @@ def parse_args():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--kv-split", type=int, default=0)
     ap.add_argument("--attn-flags", type=int, default=0)
+    ap.add_argument("--no-lm-head", action="store_true", help="skip the timing of the fused head + argmax kernel")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one device copy of this many MiB (a known-size kernel to calibrate profiler byte counters)")
     ap.add_argument("--sets", type=int, default=0, help="cache sets to rotate over (0 = enough to exceed 640 MB)")
@@ -288,6 +289,40 @@ def main():
                  "hbm_gbs": by / (att_us * 1e-6) / 1e9, "mfma_tflops": fl / (att_us * 1e-6) / 1e12,
                  "measured_stream_read_gbs": stream_gbs})
 
+    # beside the step (not part of it: the step takes logits as input): the teacher head fused with the greedy
+    # choice on the step's node rows, a 7B-class head (D = 4096, V = the workload's vocabulary), weights packed once
+    head = None
+    if not a.no_lm_head:
+        Dm, V = 4096, wl.V
+        hid = torch.randn((wl.B, wl.T_max, Dm), device="cuda:0").to(torch.bfloat16)
+        nsets = max(1, -(-640 * 2 ** 20 // (2 * V * Dm)))     # rotate so that the weights stream from HBM
+        packed = []
+        for _ in range(nsets):
+            wt = (torch.randn((V, Dm), device="cuda:0") / 64).to(torch.bfloat16)
+            packed.append(api.pack_lm_head(wt))
+            del wt
+        hws = torch.empty((max(256, int(api.lib().etv_lm_head_argmax_workspace_bytes(wl.B, wl.T_max, V))),),
+                          dtype=torch.uint8, device="cuda:0")
+        hout = dict(argmax=torch.empty((wl.B, wl.T_max), dtype=torch.int32, device="cuda:0"),
+                    maxval=torch.empty((wl.B, wl.T_max), dtype=torch.float32, device="cuda:0"))
+
+        def head_call(i):
+            api.lm_head_argmax(hid, packed[i % nsets], st.n_nodes, V=V, workspace=hws, out=hout)
+        for i in range(3):
+            head_call(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(20):
+            head_call(i)
+        e1.record()
+        torch.cuda.synchronize()
+        head_us = e0.elapsed_time(e1) * 1e3 / 20
+        head = {"kernel": "lm_head_argmax (head GEMM + argmax, logits never written; + finishing launch)",
+                "rows": int(wl.B * wl.T_max), "D": Dm, "V": V, "us_per_call": head_us,
+                "weight_bytes": 2 * V * Dm, "hbm_gbs": 2 * V * Dm / (head_us * 1e-6) / 1e9,
+                "frac_of_peak": 2 * V * Dm / (head_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        del packed
+
     cpu = None if a.skip_cpu else cpu_baseline(a.workload, a.layers)
     line = {
         "metric": "tree-verify tokens/s (batch x tree nodes)", "value": tokens_per_step / (ms_per_step * 1e-3),
@@ -296,7 +331,7 @@ def main():
         "config": {"workload": f"{a.workload}: {desc_text}", "layers": a.layers, "tokens_per_step": tokens_per_step,
                    "launch": "eager" if a.no_graph else "hip-graph replay", "cache_sets": st.nsets,
                    "cache_bytes": st.cache_bytes, "kv_split": a.kv_split},
-        "roofline": roof, "cpu_baseline": cpu,
+        "roofline": roof, "cpu_baseline": cpu, "lm_head_argmax": head,
     }
     print(json.dumps(line))
 

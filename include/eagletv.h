@@ -209,6 +209,8 @@ ETV_API int32_t etv_safe_gather_paths(const int32_t *retrieve, const int32_t *n_
  *  logits float [B, T_max, V] (no NaN); tokens int32 [B, T_max]; retrieve int32 [B, L_max, W];
  *  argmax int32 [B,T_max]; len int32 [B,L_max]; best, accept_len, bonus int32 [B]; acc_nodes int32 [B,W].
  *  workspace: etv_evaluate_posterior_workspace_bytes(B, T_max, V) bytes.
+ *  logits may be NULL: then argmax[B,T_max] is an input (the teacher's choice per node, e.g. from
+ *  etv_lm_head_argmax), V is ignored and no workspace is needed.
  * Requires 1 <= T_max <= ETV_MAX_TREE, W >= 1, L_max >= 1, 0 <= dummy < T_max.
  * ------------------------------------------------------------------------- */
 ETV_API size_t etv_evaluate_posterior_workspace_bytes(int32_t B, int32_t T_max, int32_t V);
@@ -256,6 +258,39 @@ ETV_API int32_t etv_commit_accepted_kv(const etv_commit_desc *h_desc, const void
                                int32_t *status, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * lm_head_argmax -- Section 3.3 ("Execution view", "Mapping teacher outputs to
+ * node verification scores") and Section 5.1 (greedy decoding): the teacher's
+ * head turns the hidden state of every tree node into logits over the
+ * vocabulary, and greedy acceptance needs only their argmax.  One pass over the
+ * head weights; the logits are never written to memory.
+ *   logits[b,k,v] = sum_c hidden[b,k,c] * weight[v,c]   (bf16 inputs, fp32 accumulation)
+ *   argmax[b,k]   = lowest v among the maxima; -1 for padded rows (k >= n_nodes[b])
+ *
+ *  hidden   in  bf16 [B, T_max, D]     16-byte aligned
+ *  weight   in  bf16 [V, D] row-major (weight_packed = 0), or the same weights packed once by
+ *               etv_pack_lm_head (weight_packed = 1), which streams a quarter faster; 16-byte aligned
+ *  n_nodes  in  int32 [B]
+ *  argmax   out int32 [B, T_max]       can be handed to etv_evaluate_posterior / etv_verify_epilogue
+ *                                      in place of logits (see there)
+ *  maxval   out float [B, T_max]       the maximal logit, -inf for padded rows     nullable
+ *  workspace: etv_lm_head_argmax_workspace_bytes(B, T_max, V) bytes.
+ * Requires D % 128 == 0.  Built for the row counts of a verify step (B * T_max up to a few
+ * hundred): every group of 64 rows streams the weights once (repeats come from L2).
+ * ------------------------------------------------------------------------- */
+ETV_API size_t etv_lm_head_argmax_workspace_bytes(int32_t B, int32_t T_max, int32_t V);
+
+ETV_API int32_t etv_lm_head_argmax(const void *hidden, const void *weight, int32_t weight_packed,
+                           const int32_t *n_nodes, int32_t B, int32_t T_max, int32_t D, int32_t V, int32_t *argmax,
+                           float *maxval, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Head weights in the order etv_lm_head_argmax reads them: tiles of 128 vocabulary rows x 128 elements, each
+ * 32 KiB of consecutive memory ([ceil(V/128)][D/128][128][128], rows past V are zero).  Done once per set of
+ * weights.  packed: etv_lm_head_packed_bytes(V, D) bytes, 16-byte aligned.  Requires D % 128 == 0. */
+ETV_API size_t etv_lm_head_packed_bytes(int32_t V, int32_t D);
+
+ETV_API int32_t etv_pack_lm_head(const void *weight, int32_t V, int32_t D, void *packed, void *stream);
+
+/* ---------------------------------------------------------------------------
  * verify_epilogue -- everything after the teacher forward in three launches
  * instead of five: the safe gather (Section 3.2 "Dummy-root indexing"), greedy
  * acceptance (Sections 2.3 and 5.1) and the commit of the accepted rows
@@ -264,7 +299,8 @@ ETV_API int32_t etv_commit_accepted_kv(const etv_commit_desc *h_desc, const void
  * layouts, outputs and status bits are those of etv_safe_gather_paths,
  * etv_evaluate_posterior and etv_commit_accepted_kv called in that order with
  * W = h_desc->W as the row length of retrieve, acc_nodes and slot_map; the
- * results are identical.  safe, pvalid and (src, gathered) are nullable as there.
+ * results are identical.  safe, pvalid and (src, gathered) are nullable as there;
+ * logits may be NULL as there (argmax is then an input).
  * workspace: etv_evaluate_posterior_workspace_bytes(B, T_max, V) bytes.
  * Requires T_max <= ETV_MAX_TREE and W <= ETV_MAX_TREE.
  * ------------------------------------------------------------------------- */

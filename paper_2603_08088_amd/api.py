@@ -32,7 +32,8 @@ EXPORTS = ("etv_status_string", "etv_version", "etv_last_hip_error", "etv_hbm_re
            "etv_tensorize_tree",
            "etv_tree_verify_attention_workspace_bytes", "etv_tree_verify_attention", "etv_safe_gather_paths",
            "etv_evaluate_posterior_workspace_bytes", "etv_evaluate_posterior", "etv_commit_accepted_kv",
-           "etv_verify_epilogue")
+           "etv_verify_epilogue", "etv_lm_head_argmax_workspace_bytes", "etv_lm_head_argmax",
+           "etv_lm_head_packed_bytes", "etv_pack_lm_head")
 
 
 class AttnDesc(C.Structure):
@@ -79,6 +80,14 @@ def lib():
         l.etv_tree_verify_attention.argtypes = [C.POINTER(AttnDesc)] + [vp] * 12 + [sz, vp]
         l.etv_safe_gather_paths.restype = i32
         l.etv_safe_gather_paths.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, sz, vp, vp, vp, vp]
+        l.etv_lm_head_argmax_workspace_bytes.restype = sz
+        l.etv_lm_head_argmax_workspace_bytes.argtypes = [i32, i32, i32]
+        l.etv_lm_head_argmax.restype = i32
+        l.etv_lm_head_argmax.argtypes = [vp, vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+        l.etv_lm_head_packed_bytes.restype = sz
+        l.etv_lm_head_packed_bytes.argtypes = [i32, i32]
+        l.etv_pack_lm_head.restype = i32
+        l.etv_pack_lm_head.argtypes = [vp, i32, i32, vp, vp]
         l.etv_verify_epilogue.restype = i32
         l.etv_verify_epilogue.argtypes = [C.POINTER(CommitDesc), vp, i32, vp, vp, i32, i32, vp, sz] + [vp] * 21 + [sz, vp]
         l.etv_evaluate_posterior_workspace_bytes.restype = sz
@@ -238,25 +247,63 @@ def evaluate_posterior_workspace_bytes(B: int, T_max: int, V: int) -> int:
 def evaluate_posterior(logits, tokens, retrieve, n_nodes, dummy: int = 0, workspace=None,
                        out: Optional[Dict[str, torch.Tensor]] = None):
     """logits f32 [B,T,V]; tokens int32 [B,T]; retrieve int32 [B,L,W] -> argmax, len, best, accept_len,
-    acc_nodes, bonus (all int32)."""
-    B, T, V = logits.shape
+    acc_nodes, bonus (all int32).  With logits=None, out["argmax"] is an input (e.g. from lm_head_argmax)."""
+    if logits is None:
+        (B, T), V = tokens.shape, 0
+        assert out is not None and out.get("argmax") is not None
+    else:
+        B, T, V = logits.shape
     _, L, W = retrieve.shape
-    dev = logits.device
+    dev = tokens.device
     o = out or {}
     i32 = dict(dtype=torch.int32, device=dev)
-    g = o.get("argmax") if out else torch.empty((B, T), **i32)
-    ln = o.get("len") if out else torch.empty((B, L), **i32)
-    best = o.get("best") if out else torch.empty((B,), **i32)
-    A = o.get("accept_len") if out else torch.empty((B,), **i32)
-    acc = o.get("acc_nodes") if out else torch.empty((B, W), **i32)
-    bonus = o.get("bonus") if out else torch.empty((B,), **i32)
-    if workspace is None:
+    def get(name, shape):
+        t = o.get(name)
+        return t if t is not None else torch.empty(shape, **i32)
+    g, ln, best = get("argmax", (B, T)), get("len", (B, L)), get("best", (B,))
+    A, acc, bonus = get("accept_len", (B,)), get("acc_nodes", (B, W)), get("bonus", (B,))
+    if workspace is None and logits is not None:
         workspace = torch.empty((max(256, evaluate_posterior_workspace_bytes(B, T, V)),), dtype=torch.uint8, device=dev)
     rc = lib().etv_evaluate_posterior(_ptr(logits), _ptr(tokens), _ptr(retrieve), _ptr(n_nodes), B, T, V, L, W,
                                       dummy, _ptr(g), _ptr(ln), _ptr(best), _ptr(A), _ptr(acc), _ptr(bonus),
-                                      _ptr(workspace), workspace.numel(), _stream())
+                                      _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream())
     _check("etv_evaluate_posterior", rc)
     return dict(argmax=g, len=ln, best=best, accept_len=A, acc_nodes=acc, bonus=bonus)
+
+
+def pack_lm_head(weight: torch.Tensor) -> torch.Tensor:
+    """weight bf16 [V,D] -> the same weights in the tile order lm_head_argmax streams fastest (flat bf16 tensor)."""
+    V, D = weight.shape
+    n = int(lib().etv_lm_head_packed_bytes(V, D))
+    if n == 0:
+        raise EtvError("etv_lm_head_packed_bytes", -2)
+    packed = torch.empty((n // 2,), dtype=weight.dtype, device=weight.device)
+    _check("etv_pack_lm_head", lib().etv_pack_lm_head(_ptr(weight), V, D, _ptr(packed), _stream()))
+    return packed
+
+
+def lm_head_argmax(hidden, weight, n_nodes, *, V: Optional[int] = None, want_max: bool = True, workspace=None,
+                   out: Optional[Dict[str, torch.Tensor]] = None):
+    """hidden bf16 [B,T,D]; weight bf16 [V,D], or the flat tensor of pack_lm_head together with V
+    -> argmax int32 [B,T] (-1 for padding), maxval float32 [B,T]."""
+    B, T, D = hidden.shape
+    packed = weight.dim() == 1
+    if not packed:
+        V = weight.shape[0]
+    assert V is not None
+    dev = hidden.device
+    o = out or {}
+    g = o.get("argmax")
+    if g is None:
+        g = torch.empty((B, T), dtype=torch.int32, device=dev)
+    mx = o.get("maxval") if out else (torch.empty((B, T), dtype=torch.float32, device=dev) if want_max else None)
+    if workspace is None:
+        workspace = torch.empty((max(256, int(lib().etv_lm_head_argmax_workspace_bytes(B, T, V))),), dtype=torch.uint8,
+                                device=dev)
+    rc = lib().etv_lm_head_argmax(_ptr(hidden), _ptr(weight), int(packed), _ptr(n_nodes), B, T, D, V, _ptr(g), _ptr(mx),
+                                  _ptr(workspace), workspace.numel(), _stream())
+    _check("etv_lm_head_argmax", rc)
+    return dict(argmax=g, maxval=mx)
 
 
 def _commit_desc(kt, k_cache, block_table, W: int) -> CommitDesc:
@@ -278,10 +325,14 @@ def verify_epilogue(logits, tokens, retrieve, n_nodes, kt, vt, k_cache, v_cache,
                     post_out: Optional[Dict[str, torch.Tensor]] = None,
                     commit_out: Optional[Dict[str, torch.Tensor]] = None):
     """safe_gather_paths + evaluate_posterior + commit_accepted_kv in three launches; same tensors and results.
-    Returns (gather dict, posterior dict, commit dict)."""
-    B, T, V = logits.shape
+    With logits=None, post_out["argmax"] is an input.  Returns (gather dict, posterior dict, commit dict)."""
+    if logits is None:
+        (B, T), V = tokens.shape, 0
+        assert post_out is not None and post_out.get("argmax") is not None
+    else:
+        B, T, V = logits.shape
     _, L, W = retrieve.shape
-    dev = logits.device
+    dev = tokens.device
     i32 = dict(dtype=torch.int32, device=dev)
     go, po, co = gather_out or {}, post_out or {}, commit_out or {}
 
@@ -296,14 +347,15 @@ def verify_epilogue(logits, tokens, retrieve, n_nodes, kt, vt, k_cache, v_cache,
     g, ln, best = get(po, "argmax", (B, T)), get(po, "len", (B, L)), get(po, "best", (B,))
     A, acc, bonus = get(po, "accept_len", (B,)), get(po, "acc_nodes", (B, W)), get(po, "bonus", (B,))
     plo, slot, status = get(co, "prefix_len_out", (B,)), get(co, "slot_map", (B, W)), get(co, "status", (B,))
-    if workspace is None:
+    if workspace is None and logits is not None:
         workspace = torch.empty((max(256, evaluate_posterior_workspace_bytes(B, T, V)),), dtype=torch.uint8, device=dev)
     dsc = _commit_desc(kt, k_cache, block_table, W)
     rc = lib().etv_verify_epilogue(C.byref(dsc), _ptr(logits), V, _ptr(tokens), _ptr(retrieve), L, dummy, _ptr(src),
                                    row_bytes, _ptr(safe), _ptr(pvalid), _ptr(gathered), _ptr(g), _ptr(ln), _ptr(best),
                                    _ptr(A), _ptr(acc), _ptr(bonus), _ptr(kt), _ptr(vt), _ptr(k_cache), _ptr(v_cache),
                                    _ptr(block_table), _ptr(prefix_len), _ptr(capacity), _ptr(n_nodes), _ptr(plo),
-                                   _ptr(slot), _ptr(status), _ptr(workspace), workspace.numel(), _stream())
+                                   _ptr(slot), _ptr(status), _ptr(workspace),
+                                   workspace.numel() if workspace is not None else 0, _stream())
     _check("etv_verify_epilogue", rc)
     return (dict(safe=safe, pvalid=pvalid, gathered=gathered),
             dict(argmax=g, len=ln, best=best, accept_len=A, acc_nodes=acc, bonus=bonus),

@@ -48,7 +48,7 @@ __device__ __forceinline__ MaxIdx better(MaxIdx a, MaxIdx b) {
 constexpr int kChunk = 4096;  // floats of one logit row scanned by one workgroup (16 KiB)
 
 // Acceptance for sequence b by one workgroup of 256 threads (thread t): finish the argmax from the per-chunk
-// partials, walk every path with guarded compares, reduce to the best path (longest, lowest index on ties),
+// partials (or, with pval == nullptr, take argmax[] as given), walk every path with guarded compares, reduce to the best path (longest, lowest index on ties),
 // write argmax / len / best / accept_len / acc_nodes / bonus.  Leaves the accepted length in *s_A and the
 // accepted node row (W entries) in s_acc (both in LDS, valid after the call for every thread).
 // Section 2.3 / 5.1: greedy acceptance of the longest root-to-leaf prefix.
@@ -65,14 +65,18 @@ __device__ __forceinline__ void posterior_for_sequence(
     for (int node = t; node < T_max; node += 256) {
         int32_t g = -1;
         if (node < n) {
-            size_t o = ((size_t)b * T_max + node) * chunks;
-            MaxIdx m = {pval[o], pidx[o]};
-            for (int c = 1; c < chunks; c++) m = better(m, MaxIdx{pval[o + c], pidx[o + c]});
-            g = m.i;
+            if (pval) {
+                size_t o = ((size_t)b * T_max + node) * chunks;
+                MaxIdx m = {pval[o], pidx[o]};
+                for (int c = 1; c < chunks; c++) m = better(m, MaxIdx{pval[o + c], pidx[o + c]});
+                g = m.i;
+            } else {  // the caller already has the teacher's choice per node (etv_lm_head_argmax)
+                g = argmax[(size_t)b * T_max + node];
+            }
         }
         s_g[node] = g;
         s_tok[node] = tokens[(size_t)b * T_max + node];
-        argmax[(size_t)b * T_max + node] = g;
+        if (pval) argmax[(size_t)b * T_max + node] = g;
     }
     __syncthreads();
     int my_len = -1, my_path = 0x7fffffff;

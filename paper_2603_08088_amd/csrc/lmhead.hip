@@ -1,0 +1,322 @@
+// lm_head_argmax: teacher head and greedy choice in one pass, logits never written to memory.
+// Section 3.3 ("Execution view", "Mapping teacher outputs to node verification scores"): the teacher turns
+// the hidden state of every tree node into logits over the vocabulary; Section 5.1: greedy decoding needs only
+// their argmax.  For the 60..128 rows of a verify step this is a weight-streaming product: each head weight is
+// read from HBM once (2 * V * D bytes) and the arithmetic intensity is the row count, so the bound is HBM.
+//
+// Work unit: 128 vocabulary rows x up to 64 node rows.  The contraction runs over D in steps of 128: a step's
+// weight tile (128 rows x 256 B = 32 KiB, 256 contiguous bytes of every row) and hidden tile (64 rows x 256 B)
+// go to LDS with asynchronous direct-to-LDS loads into a ring of three stages, one barrier per step.
+// Wavefront w of 8 owns vocabulary block w % 4 (32 rows) and node chunk w / 4 (32 rows).
+// C^T[vocab, node] = W . H^T on v_mfma_f32_32x32x16_bf16: A = weight rows, B = hidden rows, so a node is an
+// accumulator column and its maximum over the vocabulary stays in one lane pair.  The 16-byte chunk c of tile
+// row r sits at chunk position c ^ (r & 15), which spreads the fragment reads of 32 consecutive rows over the
+// LDS banks.  More than 64 rows run as further row groups: they stream the weights again, placed so that the
+// groups of one vocabulary tile share an XCD and the repeat comes from its L2.
+//
+// Weight layout.  With row-major [V, D] weights a step reads 128 pieces of 256 B that lie 2 * D bytes apart,
+// and the stream reaches 4.6-4.8 TB/s; with the weights packed once into tiles ([V/128][D/128][128 rows][128],
+// etv_pack_lm_head) a step's tile is 32 KiB of consecutive memory and the same kernel reaches 5.5-5.8 TB/s.
+// Both layouts are accepted.
+#include "etv_common.h"
+
+namespace etv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 lh_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float lh_f32x16;
+
+constexpr int LH_VT = 128;   // vocabulary rows per workgroup
+constexpr int LH_RT = 64;    // node rows per workgroup (2 chunks of 32)
+constexpr int LH_KC = 128;   // contraction elements per step
+constexpr int LH_ROWB = LH_KC * 2;               // bytes of a tile row
+constexpr int LH_W_BYTES = LH_VT * LH_ROWB;      // 32 KiB
+constexpr int LH_STAGE = LH_W_BYTES + LH_RT * LH_ROWB;  // 48 KiB
+constexpr int LH_NS = 3;     // ring stages (144 KiB)
+
+extern __shared__ __attribute__((aligned(1024))) uint8_t lh_smem[];
+
+__device__ __forceinline__ void lh_async_load16(const void *sbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n" ::"v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void lh_wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+struct LhParams {
+    const uint8_t *hidden;   // [rows_total, D] bf16
+    const uint8_t *weight;   // [V, D] bf16
+    const int32_t *n_nodes;  // [B]
+    float *pval;             // [rows_total, tiles]
+    int32_t *pidx;
+    int rows_total, T_max, D, V, tiles, groups;
+    int packed;  // weight layout: 0 = [V, D] row-major, 1 = tiles of etv_pack_lm_head
+};
+
+// wait until at most n of the wavefront's loads are outstanding, n = (steps ahead) * (loads per step)
+__device__ __forceinline__ void lh_wait(int n) {
+    switch (n) {
+    case 4: lh_wait_vmcnt<4>(); break;
+    case 5: lh_wait_vmcnt<5>(); break;
+    case 6: lh_wait_vmcnt<6>(); break;
+    default: lh_wait_vmcnt<0>(); break;
+    }
+}
+
+// 1-D grid over (vocabulary tile, row group).  Workgroups go to the 8 XCDs round-robin by id; the row groups of
+// one vocabulary tile get ids that differ by 8, so they run at the same time on one XCD and the second reader
+// of a weight line finds it in that XCD's L2.
+__global__ void __launch_bounds__(512, 1) lm_head_argmax_kernel(LhParams p) {
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lh_smem;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c32 = lane & 31, hh = lane >> 5;
+    const int rest = blockIdx.x >> 3;
+    const int group = rest % p.groups;
+    const int tile = (rest / p.groups) * 8 + (blockIdx.x & 7);
+    if (tile >= p.tiles) return;  // uniform over the workgroup
+    const int v0 = tile * LH_VT;
+    const int r0 = group * LH_RT;
+    const int nrows = min(LH_RT, p.rows_total - r0);   // >= 1
+    const int nchunks = (nrows + 31) >> 5;
+    const int steps = p.D / LH_KC;
+
+    // Loads.  A 1 KiB unit = 4 tile rows x 256 B; lane i fetches row i / 16 of the unit and the source chunk
+    // that belongs at chunk position i % 16, i.e. chunk (i % 16) ^ (row & 15).  Units 0..31 are weight rows,
+    // 32..47 hidden rows; wavefront w issues units w, w + 8, ... : the row within the tile is 4 * unit + i / 16,
+    // so row & 15 = (4 * w + i / 16) & 15 for every one of them.  Rows past the end of the vocabulary / of the
+    // node rows re-read the last valid row (their results are masked).
+    const int l_row = lane >> 4;
+    const uint32_t lane_col = (uint32_t)(((lane & 15) ^ ((4 * wave + l_row) & 15)) * 16);
+    const size_t row_bytes = (size_t)p.D * 2;
+    uint32_t voff[6];
+    const uint8_t *sbase[6];
+    bool unit_on[6];
+#pragma unroll
+    for (int u = 0; u < 6; u++) {
+        const int unit = wave + 8 * u;
+        if (u < 4) {
+            if (p.packed) {  // the tile of step st: 32 KiB at (tile * steps + st) * 32 KiB, unit after unit
+                sbase[u] = p.weight + (size_t)tile * steps * LH_W_BYTES + (size_t)unit * 1024;
+                voff[u] = (uint32_t)(l_row * LH_ROWB) + lane_col;
+            } else {
+                const int vrow = min(v0 + 4 * unit + l_row, p.V - 1);
+                const int vfirst = min(v0 + 4 * unit, p.V - 1);
+                sbase[u] = p.weight + (size_t)vfirst * row_bytes;
+                voff[u] = (uint32_t)((size_t)(vrow - vfirst) * row_bytes) + lane_col;
+            }
+            unit_on[u] = true;
+        } else {
+            const int hu = unit - 32;  // hidden unit: rows 4 * hu ..
+            const int last = r0 + nrows - 1;
+            const int rrow = min(r0 + 4 * hu + l_row, last);
+            const int rfirst = min(r0 + 4 * hu, last);
+            sbase[u] = p.hidden + (size_t)rfirst * row_bytes;
+            voff[u] = (uint32_t)((size_t)(rrow - rfirst) * row_bytes) + lane_col;
+            unit_on[u] = 4 * hu < nrows;  // hidden units beyond the rows of this group are not loaded at all
+        }
+    }
+    const int loads_per_step = 4 + (unit_on[4] ? 1 : 0) + (unit_on[5] ? 1 : 0);
+    auto issue = [&](int st) {
+        const uint32_t dst = smem_addr + (uint32_t)(st % LH_NS) * LH_STAGE + (uint32_t)wave * 1024;
+        const size_t koff = (size_t)st * LH_ROWB;                               // row-major: next 256 B of every row
+        const size_t woff = p.packed ? (size_t)st * LH_W_BYTES : koff;          // packed: next 32 KiB tile
+#pragma unroll
+        for (int u = 0; u < 6; u++)
+            if (unit_on[u]) lh_async_load16(sbase[u] + (u < 4 ? woff : koff), voff[u], dst + u * 8192);
+    };
+    constexpr int PD = LH_NS - 1;
+    for (int st = 0; st < PD && st < steps; st++) issue(st);
+
+    // Fragment offsets: A = weight rows of vocabulary block vb, B = hidden rows of chunk cg; lane holds row
+    // c32 and the 8 contraction values at 16-byte chunk 2 * kk + hh of the 128-element step.
+    const int vb = wave & 3, cg = wave >> 2;
+    const uint32_t a_row = (uint32_t)((32 * vb + c32) * LH_ROWB);
+    const uint32_t b_row = (uint32_t)(LH_W_BYTES + (32 * cg + c32) * LH_ROWB);
+    const int sw = c32 & 15;
+    const bool has = cg < nchunks;
+
+    lh_f32x16 acc0, acc1;  // two chains over the even / odd contraction steps
+#pragma unroll
+    for (int i = 0; i < 16; i++) { acc0[i] = 0.f; acc1[i] = 0.f; }
+
+    for (int st = 0; st < steps; st++) {
+        // loads of the younger step may stay outstanding
+        lh_wait(min(PD - 1, steps - 1 - st) * loads_per_step);
+        __builtin_amdgcn_s_barrier();  // step st is in LDS for everyone; the stage of step st - 1 is free
+        asm volatile("" ::: "memory");
+        if (st + PD < steps) issue(st + PD);
+        const uint8_t *stage = lh_smem + (st % LH_NS) * LH_STAGE;
+        if (!has) continue;
+        lh_bf16x8 a[8], b[8];
+#pragma unroll
+        for (int kk = 0; kk < 8; kk++) {
+            const int col = ((2 * kk + hh) ^ sw) << 4;
+            a[kk] = *reinterpret_cast<const lh_bf16x8 *>(stage + a_row + col);
+            b[kk] = *reinterpret_cast<const lh_bf16x8 *>(stage + b_row + col);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 8; kk += 2) {
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], b[kk], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk + 1], b[kk + 1], acc1, 0, 0, 0);
+        }
+    }
+
+    // Epilogue: per node column the maximum over this wavefront's 32 vocabulary rows (accumulator element i of
+    // lane half hh is vocabulary row 8 * (i / 4) + 4 * hh + i % 4: ascending in i), then over the two lane
+    // halves, then over the four vocabulary blocks through LDS.  Lowest index wins among equals.
+    __builtin_amdgcn_s_barrier();  // the ring is free
+    float *s_val = reinterpret_cast<float *>(lh_smem);                    // [4 blocks][64 rows]
+    int32_t *s_idx = reinterpret_cast<int32_t *>(lh_smem + 4 * LH_RT * 4);
+    if (has) {
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int v = v0 + 32 * vb + 8 * (i >> 2) + 4 * hh + (i & 3);
+            const float x = (v < p.V) ? acc0[i] + acc1[i] : -INFINITY;
+            if (x > bv || (bi == 0x7fffffff && v < p.V)) { bv = x; bi = v; }
+        }
+        const float ov = __shfl_xor(bv, 32);
+        const int oi = __shfl_xor(bi, 32);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        if (hh == 0) {
+            const int rl = 32 * cg + c32;
+            s_val[vb * LH_RT + rl] = bv;
+            s_idx[vb * LH_RT + rl] = bi;
+        }
+    }
+    __syncthreads();
+    if (tid < nrows) {
+        float bv = s_val[tid];
+        int bi = s_idx[tid];
+#pragma unroll
+        for (int q = 1; q < 4; q++) {
+            const float ov = s_val[q * LH_RT + tid];
+            const int oi = s_idx[q * LH_RT + tid];
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        const size_t o = (size_t)(r0 + tid) * p.tiles + tile;
+        p.pval[o] = bv;
+        p.pidx[o] = bi;
+    }
+}
+
+// One wavefront per node row: reduce the per-tile partials (lowest index among equals); padded rows give -1.
+__global__ void __launch_bounds__(256) lm_head_finish_kernel(const float *__restrict__ pval,
+                                                            const int32_t *__restrict__ pidx, int tiles,
+                                                            const int32_t *__restrict__ n_nodes, int rows_total,
+                                                            int T_max, int32_t *__restrict__ argmax,
+                                                            float *__restrict__ maxval) {
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (r >= rows_total) return;
+    const int b = r / T_max, k = r - b * T_max;
+    if (k >= clampi(n_nodes[b], 0, T_max)) {
+        if (lane == 0) {
+            argmax[r] = -1;
+            if (maxval) maxval[r] = -INFINITY;
+        }
+        return;
+    }
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int t = lane; t < tiles; t += 64) {
+        const float v = pval[(size_t)r * tiles + t];
+        const int i = pidx[(size_t)r * tiles + t];
+        if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float ov = __shfl_xor(bv, off);
+        const int oi = __shfl_xor(bi, off);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    if (lane == 0) {
+        argmax[r] = bi;
+        if (maxval) maxval[r] = bv;
+    }
+}
+
+// Packing: out[tile][step][r][c] = weight[tile * 128 + r][step * 128 + c], zeros for rows past V.
+// One thread per 16-byte piece.
+__global__ void __launch_bounds__(256) lm_head_pack_kernel(const uint4 *__restrict__ weight, uint4 *__restrict__ out,
+                                                          int V, int D, long pieces) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= pieces) return;
+    const int steps = D / LH_KC;
+    const int c16 = (int)(i & 15);                 // 16-byte piece within the 256-byte tile row
+    const int r = (int)((i >> 4) & (LH_VT - 1));   // row within the tile
+    const long ts = i >> 11;                       // tile * steps + step
+    const int st = (int)(ts % steps);
+    const long v = (ts / steps) * LH_VT + r;
+    uint4 x = {0, 0, 0, 0};
+    if (v < V) x = weight[(v * D + (long)st * LH_KC) / 8 + c16];
+    out[i] = x;
+}
+
+}  // namespace etv
+
+extern "C" size_t etv_lm_head_packed_bytes(int32_t V, int32_t D) {
+    if (V < 1 || D < 1 || D % etv::LH_KC != 0) return 0;
+    return (((size_t)V + etv::LH_VT - 1) / etv::LH_VT) * etv::LH_VT * (size_t)D * 2;
+}
+
+extern "C" int32_t etv_pack_lm_head(const void *weight, int32_t V, int32_t D, void *packed, void *stream) {
+    using namespace etv;
+    if (!weight || !packed || V < 1 || D < 1) return ETV_ERR_INVALID_ARG;
+    if (D % LH_KC != 0) return ETV_ERR_UNSUPPORTED;
+    if ((((uintptr_t)weight) | ((uintptr_t)packed)) & 15) return ETV_ERR_INVALID_ARG;
+    const long pieces = (long)(etv_lm_head_packed_bytes(V, D) / 16);
+    const long blocks = (pieces + 255) / 256;
+    if (blocks > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(lm_head_pack_kernel, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream),
+                       static_cast<const uint4 *>(weight), static_cast<uint4 *>(packed), (int)V, (int)D, pieces);
+    return check_launch();
+}
+
+extern "C" size_t etv_lm_head_argmax_workspace_bytes(int32_t B, int32_t T_max, int32_t V) {
+    if (B < 1 || T_max < 1 || V < 1) return 0;
+    const size_t tiles = ((size_t)V + etv::LH_VT - 1) / etv::LH_VT;
+    return (size_t)B * T_max * tiles * (sizeof(float) + sizeof(int32_t));
+}
+
+extern "C" int32_t etv_lm_head_argmax(const void *hidden, const void *weight, int32_t weight_packed,
+                                      const int32_t *n_nodes, int32_t B, int32_t T_max, int32_t D, int32_t V,
+                                      int32_t *argmax, float *maxval, void *workspace, size_t workspace_bytes,
+                                      void *stream) {
+    using namespace etv;
+    if (!hidden || !weight || !n_nodes || !argmax || B < 0 || T_max < 1 || D < 1 || V < 1) return ETV_ERR_INVALID_ARG;
+    if (D % LH_KC != 0) return ETV_ERR_UNSUPPORTED;
+    if ((((uintptr_t)hidden) | ((uintptr_t)weight)) & 15) return ETV_ERR_INVALID_ARG;
+    if ((size_t)D * 2 * 8 >= (1ull << 32)) return ETV_ERR_UNSUPPORTED;
+    if (B == 0) return ETV_OK;
+    const long rows_total = (long)B * T_max;
+    const long groups = (rows_total + LH_RT - 1) / LH_RT;
+    const long tiles = ((long)V + LH_VT - 1) / LH_VT;
+    if (groups > 65535 || rows_total > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < etv_lm_head_argmax_workspace_bytes(B, T_max, V))
+        return ETV_ERR_WORKSPACE_TOO_SMALL;
+    LhParams p{};
+    p.hidden = static_cast<const uint8_t *>(hidden);
+    p.weight = static_cast<const uint8_t *>(weight);
+    p.n_nodes = n_nodes;
+    p.pval = static_cast<float *>(workspace);
+    p.pidx = reinterpret_cast<int32_t *>(p.pval + (size_t)rows_total * tiles);
+    p.rows_total = (int)rows_total; p.T_max = T_max; p.D = D; p.V = V; p.tiles = (int)tiles; p.groups = (int)groups;
+    p.packed = weight_packed ? 1 : 0;
+    constexpr size_t lds = (size_t)LH_NS * LH_STAGE;
+    static const bool lds_ok = [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&lm_head_argmax_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
+    }();
+    if (!lds_ok) return ETV_ERR_HIP;
+    hipStream_t s = as_stream(stream);
+    const long nblocks = ((tiles + 7) / 8) * groups * 8;
+    if (nblocks > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(lm_head_argmax_kernel, dim3((unsigned)nblocks), dim3(512), lds, s, p);
+    int32_t rc = check_launch();
+    if (rc != ETV_OK) return rc;
+    hipLaunchKernelGGL(lm_head_finish_kernel, dim3((unsigned)((rows_total + 3) / 4)), dim3(256), 0, s, p.pval, p.pidx,
+                       (int)tiles, n_nodes, (int)rows_total, (int)T_max, argmax, maxval);
+    return check_launch();
+}

@@ -147,24 +147,29 @@ extern "C" int32_t etv_evaluate_posterior(const float *logits, const int32_t *to
                                           int32_t L_max, int32_t W, int32_t dummy, int32_t *argmax, int32_t *len,
                                           int32_t *best, int32_t *accept_len, int32_t *acc_nodes, int32_t *bonus,
                                           void *workspace, size_t workspace_bytes, void *stream) {
-    if (!logits || !tokens || !retrieve || !n_nodes || !argmax || !len || !best || !accept_len || !acc_nodes ||
-        !bonus)
+    if (!tokens || !retrieve || !n_nodes || !argmax || !len || !best || !accept_len || !acc_nodes || !bonus)
         return ETV_ERR_INVALID_ARG;
-    if (B < 0 || T_max < 1 || V < 1 || L_max < 1 || W < 1) return ETV_ERR_INVALID_ARG;
+    if (B < 0 || T_max < 1 || (logits && V < 1) || L_max < 1 || W < 1) return ETV_ERR_INVALID_ARG;
     if (dummy < 0 || dummy >= T_max) return ETV_ERR_INVALID_ARG;
     if (T_max > ETV_MAX_TREE) return ETV_ERR_UNSUPPORTED;
     if (B == 0) return ETV_OK;
     if (B > 65535) return ETV_ERR_UNSUPPORTED;
-    size_t need = etv_evaluate_posterior_workspace_bytes(B, T_max, V);
-    if (!workspace || workspace_bytes < need) return ETV_ERR_WORKSPACE_TOO_SMALL;
-    int chunks = (V + etv::kChunk - 1) / etv::kChunk;
-    float *pval = static_cast<float *>(workspace);
-    int32_t *pidx = reinterpret_cast<int32_t *>(pval + (size_t)B * T_max * chunks);
     hipStream_t s = etv::as_stream(stream);
-    hipLaunchKernelGGL(etv::argmax_partial_kernel, dim3(chunks, T_max, B), dim3(256), 0, s, logits, n_nodes,
-                       (int)T_max, (int)V, chunks, pval, pidx);
-    int32_t rc = etv::check_launch();
-    if (rc != ETV_OK) return rc;
+    int chunks = 0;
+    float *pval = nullptr;
+    int32_t *pidx = nullptr;
+    int32_t rc;
+    if (logits) {  // without logits, argmax[] is an input
+        size_t need = etv_evaluate_posterior_workspace_bytes(B, T_max, V);
+        if (!workspace || workspace_bytes < need) return ETV_ERR_WORKSPACE_TOO_SMALL;
+        chunks = (V + etv::kChunk - 1) / etv::kChunk;
+        pval = static_cast<float *>(workspace);
+        pidx = reinterpret_cast<int32_t *>(pval + (size_t)B * T_max * chunks);
+        hipLaunchKernelGGL(etv::argmax_partial_kernel, dim3(chunks, T_max, B), dim3(256), 0, s, logits, n_nodes,
+                           (int)T_max, (int)V, chunks, pval, pidx);
+        rc = etv::check_launch();
+        if (rc != ETV_OK) return rc;
+    }
     hipLaunchKernelGGL(etv::posterior_paths_kernel, dim3(B), dim3(256), 0, s, pval, pidx, chunks, tokens, retrieve,
                        n_nodes, (int)T_max, (int)L_max, (int)W, (int)dummy, argmax, len, best, accept_len, acc_nodes,
                        bonus);
@@ -180,28 +185,33 @@ extern "C" int32_t etv_verify_epilogue(const etv_commit_desc *h, const float *lo
                                        const int32_t *prefix_len, const int32_t *capacity, const int32_t *n_nodes,
                                        int32_t *prefix_len_out, int32_t *slot_map, int32_t *status, void *workspace,
                                        size_t workspace_bytes, void *stream) {
-    if (!logits || !tokens || !retrieve || !n_nodes || !argmax || !len || !best || !accept_len || !acc_nodes ||
+    if (!tokens || !retrieve || !n_nodes || !argmax || !len || !best || !accept_len || !acc_nodes ||
         !bonus || !prefix_len || !capacity || !prefix_len_out || !slot_map || !status)
         return ETV_ERR_INVALID_ARG;
     int32_t rc = etv::check_commit_args(h, kt, vt, k_cache, v_cache, block_table);
     if (rc != ETV_OK) return rc;
-    if (V < 1 || L_max < 1) return ETV_ERR_INVALID_ARG;
+    if ((logits && V < 1) || L_max < 1) return ETV_ERR_INVALID_ARG;
     if (dummy < 0 || dummy >= h->T_max) return ETV_ERR_INVALID_ARG;
     if ((src == nullptr) != (gathered == nullptr)) return ETV_ERR_INVALID_ARG;
     if (src && row_bytes == 0) return ETV_ERR_INVALID_ARG;
     if (h->T_max > ETV_MAX_TREE || h->W > ETV_MAX_TREE) return ETV_ERR_UNSUPPORTED;
     if (h->B == 0) return ETV_OK;
     const int32_t B = h->B, T_max = h->T_max;
-    size_t need = etv_evaluate_posterior_workspace_bytes(B, T_max, V);
-    if (!workspace || workspace_bytes < need) return ETV_ERR_WORKSPACE_TOO_SMALL;
-    int chunks = (V + etv::kChunk - 1) / etv::kChunk;
-    float *pval = static_cast<float *>(workspace);
-    int32_t *pidx = reinterpret_cast<int32_t *>(pval + (size_t)B * T_max * chunks);
     hipStream_t s = etv::as_stream(stream);
-    hipLaunchKernelGGL(etv::argmax_partial_kernel, dim3(chunks, T_max, B), dim3(256), 0, s, logits, n_nodes,
-                       (int)T_max, (int)V, chunks, pval, pidx);
-    rc = etv::check_launch();
-    if (rc != ETV_OK) return rc;
+    int chunks = 0;
+    float *pval = nullptr;
+    int32_t *pidx = nullptr;
+    if (logits) {  // without logits, argmax[] is an input
+        size_t need = etv_evaluate_posterior_workspace_bytes(B, T_max, V);
+        if (!workspace || workspace_bytes < need) return ETV_ERR_WORKSPACE_TOO_SMALL;
+        chunks = (V + etv::kChunk - 1) / etv::kChunk;
+        pval = static_cast<float *>(workspace);
+        pidx = reinterpret_cast<int32_t *>(pval + (size_t)B * T_max * chunks);
+        hipLaunchKernelGGL(etv::argmax_partial_kernel, dim3(chunks, T_max, B), dim3(256), 0, s, logits, n_nodes,
+                           (int)T_max, (int)V, chunks, pval, pidx);
+        rc = etv::check_launch();
+        if (rc != ETV_OK) return rc;
+    }
     const long gather_blocks = (safe || pvalid || gathered) ? ((long)B * L_max * h->W + 3) / 4 : 0;
     if (gather_blocks + B > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(etv::verify_epilogue_kernel, dim3((unsigned)(B + gather_blocks)), dim3(256), 0, s, *h, pval, pidx, chunks, tokens, retrieve,
