@@ -209,8 +209,10 @@ ETV_API int32_t etv_safe_gather_paths(const int32_t *retrieve, const int32_t *n_
  *  logits float [B, T_max, V] (no NaN); tokens int32 [B, T_max]; retrieve int32 [B, L_max, W];
  *  argmax int32 [B,T_max]; len int32 [B,L_max]; best, accept_len, bonus int32 [B]; acc_nodes int32 [B,W].
  *  workspace: etv_evaluate_posterior_workspace_bytes(B, T_max, V) bytes.
- *  logits may be NULL: then argmax[B,T_max] is an input (the teacher's choice per node, e.g. from
- *  etv_lm_head_argmax), V is ignored and no workspace is needed.
+ *  logits may be NULL.  With V == 0, argmax[B,T_max] is then an input (the teacher's choice per node) and no
+ *  workspace is needed.  With V > 0, the workspace is the one etv_lm_head_argmax has just filled for the same
+ *  B, T_max and V when called with argmax == NULL: the choice per node is finished from it here (and written
+ *  to argmax), which saves that call's finishing launch.
  * Requires 1 <= T_max <= ETV_MAX_TREE, W >= 1, L_max >= 1, 0 <= dummy < T_max.
  * ------------------------------------------------------------------------- */
 ETV_API size_t etv_evaluate_posterior_workspace_bytes(int32_t B, int32_t T_max, int32_t V);
@@ -271,7 +273,8 @@ ETV_API int32_t etv_commit_accepted_kv(const etv_commit_desc *h_desc, const void
  *               etv_pack_lm_head (weight_packed = 1), which streams a quarter faster; 16-byte aligned
  *  n_nodes  in  int32 [B]
  *  argmax   out int32 [B, T_max]       can be handed to etv_evaluate_posterior / etv_verify_epilogue
- *                                      in place of logits (see there)
+ *                                      in place of logits (see there).  NULL: stop after the weight pass
+ *                                      and leave the per-tile maxima in the workspace for those calls
  *  maxval   out float [B, T_max]       the maximal logit, -inf for padded rows     nullable
  *  workspace: etv_lm_head_argmax_workspace_bytes(B, T_max, V) bytes.
  * Requires D % 128 == 0.  Built for the row counts of a verify step (B * T_max up to a few

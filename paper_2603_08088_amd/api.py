@@ -245,12 +245,13 @@ def evaluate_posterior_workspace_bytes(B: int, T_max: int, V: int) -> int:
 
 
 def evaluate_posterior(logits, tokens, retrieve, n_nodes, dummy: int = 0, workspace=None,
-                       out: Optional[Dict[str, torch.Tensor]] = None):
+                       out: Optional[Dict[str, torch.Tensor]] = None, head_V: int = 0):
     """logits f32 [B,T,V]; tokens int32 [B,T]; retrieve int32 [B,L,W] -> argmax, len, best, accept_len,
-    acc_nodes, bonus (all int32).  With logits=None, out["argmax"] is an input (e.g. from lm_head_argmax)."""
+    acc_nodes, bonus (all int32).  With logits=None, out["argmax"] is an input (e.g. from lm_head_argmax), or,
+    with head_V > 0, `workspace` is the one lm_head_argmax(..., finish=False) returned for that vocabulary size."""
     if logits is None:
-        (B, T), V = tokens.shape, 0
-        assert out is not None and out.get("argmax") is not None
+        (B, T), V = tokens.shape, int(head_V)
+        assert workspace is not None if V else (out is not None and out.get("argmax") is not None)
     else:
         B, T, V = logits.shape
     _, L, W = retrieve.shape
@@ -283,9 +284,10 @@ def pack_lm_head(weight: torch.Tensor) -> torch.Tensor:
 
 
 def lm_head_argmax(hidden, weight, n_nodes, *, V: Optional[int] = None, want_max: bool = True, workspace=None,
-                   out: Optional[Dict[str, torch.Tensor]] = None):
+                   out: Optional[Dict[str, torch.Tensor]] = None, finish: bool = True):
     """hidden bf16 [B,T,D]; weight bf16 [V,D], or the flat tensor of pack_lm_head together with V
-    -> argmax int32 [B,T] (-1 for padding), maxval float32 [B,T]."""
+    -> argmax int32 [B,T] (-1 for padding), maxval float32 [B,T].  finish=False stops after the weight pass and
+    returns the workspace, to be handed to evaluate_posterior / verify_epilogue with head_V=V."""
     B, T, D = hidden.shape
     packed = weight.dim() == 1
     if not packed:
@@ -300,10 +302,11 @@ def lm_head_argmax(hidden, weight, n_nodes, *, V: Optional[int] = None, want_max
     if workspace is None:
         workspace = torch.empty((max(256, int(lib().etv_lm_head_argmax_workspace_bytes(B, T, V))),), dtype=torch.uint8,
                                 device=dev)
-    rc = lib().etv_lm_head_argmax(_ptr(hidden), _ptr(weight), int(packed), _ptr(n_nodes), B, T, D, V, _ptr(g), _ptr(mx),
+    rc = lib().etv_lm_head_argmax(_ptr(hidden), _ptr(weight), int(packed), _ptr(n_nodes), B, T, D, V,
+                                  _ptr(g) if finish else None, _ptr(mx) if finish else None,
                                   _ptr(workspace), workspace.numel(), _stream())
     _check("etv_lm_head_argmax", rc)
-    return dict(argmax=g, maxval=mx)
+    return dict(argmax=g, maxval=mx) if finish else dict(workspace=workspace)
 
 
 def _commit_desc(kt, k_cache, block_table, W: int) -> CommitDesc:
@@ -323,12 +326,13 @@ def verify_epilogue(logits, tokens, retrieve, n_nodes, kt, vt, k_cache, v_cache,
                     block_table=None, dummy: int = 0, src: Optional[torch.Tensor] = None, workspace=None,
                     gather_out: Optional[Dict[str, torch.Tensor]] = None,
                     post_out: Optional[Dict[str, torch.Tensor]] = None,
-                    commit_out: Optional[Dict[str, torch.Tensor]] = None):
+                    commit_out: Optional[Dict[str, torch.Tensor]] = None, head_V: int = 0):
     """safe_gather_paths + evaluate_posterior + commit_accepted_kv in three launches; same tensors and results.
-    With logits=None, post_out["argmax"] is an input.  Returns (gather dict, posterior dict, commit dict)."""
+    With logits=None, post_out["argmax"] is an input, or, with head_V > 0, `workspace` is the one
+    lm_head_argmax(..., finish=False) returned.  Returns (gather dict, posterior dict, commit dict)."""
     if logits is None:
-        (B, T), V = tokens.shape, 0
-        assert post_out is not None and post_out.get("argmax") is not None
+        (B, T), V = tokens.shape, int(head_V)
+        assert workspace is not None if V else (post_out is not None and post_out.get("argmax") is not None)
     else:
         B, T, V = logits.shape
     _, L, W = retrieve.shape

@@ -62,21 +62,42 @@ __device__ __forceinline__ void posterior_for_sequence(
     __shared__ int32_t s_tok[ETV_MAX_TREE];
     __shared__ int32_t s_len[256];
     __shared__ int32_t s_path[256];
-    for (int node = t; node < T_max; node += 256) {
-        int32_t g = -1;
-        if (node < n) {
-            if (pval) {
-                size_t o = ((size_t)b * T_max + node) * chunks;
-                MaxIdx m = {pval[o], pidx[o]};
-                for (int c = 1; c < chunks; c++) m = better(m, MaxIdx{pval[o + c], pidx[o + c]});
-                g = m.i;
-            } else {  // the caller already has the teacher's choice per node (etv_lm_head_argmax)
-                g = argmax[(size_t)b * T_max + node];
+    if (pval && chunks > 16) {
+        // many partials per node (the per-tile maxima of the fused head): one wavefront per node, lanes stride
+        // over the partials, shuffle reduce
+        const int lane = t & 63;
+        for (int node = t >> 6; node < T_max; node += 4) {
+            MaxIdx m = {-INFINITY, 0x7fffffff};
+            if (node < n) {
+                const size_t o = ((size_t)b * T_max + node) * chunks;
+                for (int c = lane; c < chunks; c += 64) m = better(m, MaxIdx{pval[o + c], pidx[o + c]});
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) m = better(m, MaxIdx{__shfl_xor(m.v, off), __shfl_xor(m.i, off)});
+            }
+            if (lane == 0) {
+                const int32_t g = node < n ? m.i : -1;
+                s_g[node] = g;
+                s_tok[node] = tokens[(size_t)b * T_max + node];
+                argmax[(size_t)b * T_max + node] = g;
             }
         }
-        s_g[node] = g;
-        s_tok[node] = tokens[(size_t)b * T_max + node];
-        if (pval) argmax[(size_t)b * T_max + node] = g;
+    } else {
+        for (int node = t; node < T_max; node += 256) {
+            int32_t g = -1;
+            if (node < n) {
+                if (pval) {
+                    size_t o = ((size_t)b * T_max + node) * chunks;
+                    MaxIdx m = {pval[o], pidx[o]};
+                    for (int c = 1; c < chunks; c++) m = better(m, MaxIdx{pval[o + c], pidx[o + c]});
+                    g = m.i;
+                } else {  // the caller already has the teacher's choice per node (etv_lm_head_argmax)
+                    g = argmax[(size_t)b * T_max + node];
+                }
+            }
+            s_g[node] = g;
+            s_tok[node] = tokens[(size_t)b * T_max + node];
+            if (pval) argmax[(size_t)b * T_max + node] = g;
+        }
     }
     __syncthreads();
     int my_len = -1, my_path = 0x7fffffff;

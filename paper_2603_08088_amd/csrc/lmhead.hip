@@ -285,7 +285,7 @@ extern "C" int32_t etv_lm_head_argmax(const void *hidden, const void *weight, in
                                       int32_t *argmax, float *maxval, void *workspace, size_t workspace_bytes,
                                       void *stream) {
     using namespace etv;
-    if (!hidden || !weight || !n_nodes || !argmax || B < 0 || T_max < 1 || D < 1 || V < 1) return ETV_ERR_INVALID_ARG;
+    if (!hidden || !weight || !n_nodes || B < 0 || T_max < 1 || D < 1 || V < 1) return ETV_ERR_INVALID_ARG;
     if (D % LH_KC != 0) return ETV_ERR_UNSUPPORTED;
     if ((((uintptr_t)hidden) | ((uintptr_t)weight)) & 15) return ETV_ERR_INVALID_ARG;
     if ((size_t)D * 2 * 8 >= (1ull << 32)) return ETV_ERR_UNSUPPORTED;
@@ -315,7 +315,7 @@ extern "C" int32_t etv_lm_head_argmax(const void *hidden, const void *weight, in
     if (nblocks > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(lm_head_argmax_kernel, dim3((unsigned)nblocks), dim3(512), lds, s, p);
     int32_t rc = check_launch();
-    if (rc != ETV_OK) return rc;
+    if (rc != ETV_OK || !argmax) return rc;  // without argmax the per-tile maxima stay in the workspace for the epilogue
     hipLaunchKernelGGL(lm_head_finish_kernel, dim3((unsigned)((rows_total + 3) / 4)), dim3(256), 0, s, p.pval, p.pidx,
                        (int)tiles, n_nodes, (int)rows_total, (int)T_max, argmax, maxval);
     return check_launch();

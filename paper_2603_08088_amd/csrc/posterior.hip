@@ -149,7 +149,7 @@ extern "C" int32_t etv_evaluate_posterior(const float *logits, const int32_t *to
                                           void *workspace, size_t workspace_bytes, void *stream) {
     if (!tokens || !retrieve || !n_nodes || !argmax || !len || !best || !accept_len || !acc_nodes || !bonus)
         return ETV_ERR_INVALID_ARG;
-    if (B < 0 || T_max < 1 || (logits && V < 1) || L_max < 1 || W < 1) return ETV_ERR_INVALID_ARG;
+    if (B < 0 || T_max < 1 || (logits && V < 1) || V < 0 || L_max < 1 || W < 1) return ETV_ERR_INVALID_ARG;
     if (dummy < 0 || dummy >= T_max) return ETV_ERR_INVALID_ARG;
     if (T_max > ETV_MAX_TREE) return ETV_ERR_UNSUPPORTED;
     if (B == 0) return ETV_OK;
@@ -169,6 +169,12 @@ extern "C" int32_t etv_evaluate_posterior(const float *logits, const int32_t *to
                            (int)T_max, (int)V, chunks, pval, pidx);
         rc = etv::check_launch();
         if (rc != ETV_OK) return rc;
+    } else if (V > 0) {  // the per-tile maxima left by etv_lm_head_argmax (argmax == NULL there) for this B, T_max, V
+        size_t need = etv_lm_head_argmax_workspace_bytes(B, T_max, V);
+        if (!workspace || workspace_bytes < need) return ETV_ERR_WORKSPACE_TOO_SMALL;
+        chunks = (V + 127) / 128;
+        pval = static_cast<float *>(workspace);
+        pidx = reinterpret_cast<int32_t *>(pval + (size_t)B * T_max * chunks);
     }
     hipLaunchKernelGGL(etv::posterior_paths_kernel, dim3(B), dim3(256), 0, s, pval, pidx, chunks, tokens, retrieve,
                        n_nodes, (int)T_max, (int)L_max, (int)W, (int)dummy, argmax, len, best, accept_len, acc_nodes,
@@ -190,7 +196,7 @@ extern "C" int32_t etv_verify_epilogue(const etv_commit_desc *h, const float *lo
         return ETV_ERR_INVALID_ARG;
     int32_t rc = etv::check_commit_args(h, kt, vt, k_cache, v_cache, block_table);
     if (rc != ETV_OK) return rc;
-    if ((logits && V < 1) || L_max < 1) return ETV_ERR_INVALID_ARG;
+    if ((logits && V < 1) || V < 0 || L_max < 1) return ETV_ERR_INVALID_ARG;
     if (dummy < 0 || dummy >= h->T_max) return ETV_ERR_INVALID_ARG;
     if ((src == nullptr) != (gathered == nullptr)) return ETV_ERR_INVALID_ARG;
     if (src && row_bytes == 0) return ETV_ERR_INVALID_ARG;
@@ -211,6 +217,12 @@ extern "C" int32_t etv_verify_epilogue(const etv_commit_desc *h, const float *lo
                            (int)T_max, (int)V, chunks, pval, pidx);
         rc = etv::check_launch();
         if (rc != ETV_OK) return rc;
+    } else if (V > 0) {  // the per-tile maxima left by etv_lm_head_argmax (argmax == NULL there) for this B, T_max, V
+        size_t need = etv_lm_head_argmax_workspace_bytes(B, T_max, V);
+        if (!workspace || workspace_bytes < need) return ETV_ERR_WORKSPACE_TOO_SMALL;
+        chunks = (V + 127) / 128;
+        pval = static_cast<float *>(workspace);
+        pidx = reinterpret_cast<int32_t *>(pval + (size_t)B * T_max * chunks);
     }
     const long gather_blocks = (safe || pvalid || gathered) ? ((long)B * L_max * h->W + 3) / 4 : 0;
     if (gather_blocks + B > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;

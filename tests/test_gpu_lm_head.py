@@ -144,7 +144,21 @@ def test_head_to_commit_without_logits():
                                   d.prefix_len, d.capacity, block_table=d.block_table,
                                   post_out=dict(argmax=head["argmax"]))
     p2 = api.evaluate_posterior(None, d.tokens, d.retrieve, d.n_nodes, out=dict(argmax=head["argmax"]))
+    # third way: the head stops after its weight pass and the epilogue finishes the choice per node itself
+    part = api.lm_head_argmax(_dev_bf16(hb), _dev_bf16(wb), d.n_nodes, finish=False)
+    dkc3, dvc3 = d.k_cache[None].clone(), d.v_cache[None].clone()
+    g3, p3, c3 = api.verify_epilogue(None, d.tokens, d.retrieve, d.n_nodes, d.kt[None], d.vt[None], dkc3, dvc3,
+                                     d.prefix_len, d.capacity, block_table=d.block_table,
+                                     workspace=part["workspace"], head_V=V)
+    p4 = api.evaluate_posterior(None, d.tokens, d.retrieve, d.n_nodes, workspace=part["workspace"], head_V=V)
     torch.cuda.synchronize()
+    assert np.array_equal(bits_of(p3["argmax"])[0, :int(wl.n_nodes[0])], ref_head["argmax"][0, :int(wl.n_nodes[0])])
+    assert np.all(bits_of(p3["argmax"])[0, int(wl.n_nodes[0]):] == -1)
+    for key in ("len", "best", "accept_len", "acc_nodes", "bonus"):
+        assert np.array_equal(bits_of(p3[key]), rp[key]) and np.array_equal(bits_of(p4[key]), rp[key]), key
+    for key in rc:
+        assert np.array_equal(bits_of(c3[key]), rc[key]), key
+    assert np.array_equal(bits_of(dkc3), kc) and np.array_equal(bits_of(dvc3), vc)
     n = int(wl.n_nodes[0])
     assert np.array_equal(bits_of(head["argmax"])[0, :n], ref_head["argmax"][0, :n])
     for key in ("len", "best", "accept_len", "acc_nodes", "bonus"):
