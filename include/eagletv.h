@@ -64,7 +64,7 @@ extern "C" {
 #define ETV_COMMIT_BAD_BLOCK 8 /* a needed block-table entry is outside [0, num_blocks)                */
 
 #define ETV_MAX_TREE 256       /* largest T_max of the mask builder, gather and posterior              */
-#define ETV_ATTN_MAX_TREE 128  /* largest T_max of tree_verify_attention                               */
+#define ETV_ATTN_MAX_TREE 256  /* largest T_max of tree_verify_attention                               */
 
 ETV_API const char *etv_status_string(int32_t status);
 ETV_API const char *etv_version(void);

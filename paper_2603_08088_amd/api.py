@@ -26,7 +26,7 @@ ATTN_FLAG_GENERIC = 1
 ATTN_FLAG_SMALL_WG = 2
 ATTN_FLAG_WHOLE_TILE = 4
 ATTN_FLAG_KEY_HALVES = 8
-MAX_TREE, ATTN_MAX_TREE = 256, 128
+MAX_TREE, ATTN_MAX_TREE = 256, 256
 
 EXPORTS = ("etv_status_string", "etv_version", "etv_last_hip_error", "etv_hbm_read_probe", "etv_build_tree_mask",
            "etv_tensorize_tree",

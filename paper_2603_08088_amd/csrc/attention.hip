@@ -304,7 +304,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 
 // 16 bytes per lane from global memory straight into LDS at (lds_addr + 16 * lane); asynchronous.
 __device__ __forceinline__ void async_load16(const void *gptr, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n" ::"v"(gptr), "s"(lds_addr) : "memory");
+    // lds_addr is the same in every lane; readfirstlane says so to the compiler whatever it concluded about the loop
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n" ::"v"(gptr),
+                 "s"(__builtin_amdgcn_readfirstlane(lds_addr)) : "memory");
 }
 // wait until at most N of this wavefront's vector-memory loads are outstanding (N < 64)
 template <int N>
@@ -746,12 +748,14 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     const uint16_t *qp = static_cast<const uint16_t *>(p.q);
     // Q as B operand: lane holds query row kq, d values 16*kk + 8*hh .. +7
     bf16x8 qreg[8];
-    uint64_t mbits0 = 0, mbits1 = 0;
+    uint64_t mbits0 = 0, mbits1 = 0, mbits2 = 0, mbits3 = 0;  // the row's ancestor bits, one word per tree tile
     const bool rv = active && kq < n;
     if (rv) {
         const uint64_t *mrow = p.bitmask + ((size_t)b * p.T_max + kq) * p.words;
         mbits0 = mrow[0];
         if (p.words > 1) mbits1 = mrow[1];
+        if (p.words > 2) mbits2 = mrow[2];
+        if (p.words > 3) mbits3 = mrow[3];
     }
 #pragma unroll
     for (int kk = 0; kk < 8; kk++) {
@@ -796,7 +800,9 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     };
     auto tile_vis = [&](int ti) -> uint64_t {
         if (ti < npt) return (1ull << (k1 - k0 - nfull * KT)) - 1ull;  // ragged last prefix tile: 1..63 keys
-        return (ti - npt) ? mbits1 : mbits0;                            // tree tile: the row's ancestor bits
+        const int w = ti - npt;                                         // tree tile: the row's ancestor bits
+        const uint64_t lo = (w & 1) ? mbits1 : mbits0, hi = (w & 1) ? mbits3 : mbits2;
+        return (w & 2) ? hi : lo;
     };
     bf16x8 pf[2][2], vf[2][4];
     // one tile for one wavefront, in two parts (the parts run in different ring steps for late wavefronts)

@@ -62,13 +62,13 @@ def test_generic_kernel_shapes(dtype, d, paged):
     rng = np.random.default_rng(500 + d)
     # ragged batch, padded node rows, empty prefix, several tiles + ragged tail, G in {1,2,4}
     for (Hq, Hkv, T, P, n) in [(4, 4, 15, [128, 0, 77], [15, 9, 1]), (8, 2, 70, [200, 33], [70, 64]),
-                                (4, 2, 128, [130], [128])]:
+                                (4, 2, 128, [130], [128]), (4, 2, 200, [70], [193])]:
         wl = _small(rng, len(P), T, Hq, Hkv, d, P, dtype, paged, n_nodes=n)
         _check(wl)
         _check(wl, kv_split=64)
 
 
-@pytest.mark.parametrize("T", [1, 8, 16, 31, 32, 33, 60, 64, 65, 96, 127, 128])
+@pytest.mark.parametrize("T", [1, 8, 16, 31, 32, 33, 60, 64, 65, 96, 127, 128, 129, 160, 192, 193, 255, 256])
 def test_mfma_kernel_tree_sizes(T):
     rng = np.random.default_rng(600 + T)
     wl = _small(rng, 2, T, 8, 2, 128, [300, 64], "bf16", False, n_nodes=[T, max(1, T - 3)])
