@@ -978,10 +978,11 @@ static Plan make_plan(const etv_attn_desc *h) {
             if (nw == 8 && (pl.pairs <= (kh ? 2 : 4) || (h->flags & ETV_ATTN_FLAG_SMALL_WG))) continue;
             const int wgp = (pl.pairs + cw - 1) / cw;
             const long units = (long)B * h->Hkv * wgp;
+            // candidates: every distinct number of splits, or the one split size the caller asks for
+            const int forced_tps = h->kv_split > 0 ? min(tiles, (h->kv_split + KT - 1) / KT) : 0;
             for (int ns = 1; ns <= tiles; ns++) {
-                const int tps = (tiles + ns - 1) / ns;
+                const int tps = forced_tps ? forced_tps : (tiles + ns - 1) / ns;
                 if ((tiles + tps - 1) / tps != ns) continue;
-                if (h->kv_split > 0 && tps != (h->kv_split + KT - 1) / KT) continue;
                 const long wgs = units * ns;
                 const bool alone = (nw == 4 && wgs <= 256);
                 const double slots = nw == 8 ? 256.0 : 512.0;
