@@ -232,7 +232,7 @@ def test_config4_long_context_sampled_heads():
         assert err <= 2e-2 and rel <= 2e-2
 
 
-@pytest.mark.parametrize("T,D", [(8, 4), (16, 10), (32, 6), (64, 8), (128, 10)])
+@pytest.mark.parametrize("T,D", [(8, 4), (16, 10), (32, 6), (64, 8), (128, 10), (256, 16)])
 def test_config5_sweep_cells_sampled_sequences(T, D):
     """Full batch of 32 on the GPU; the oracle recomputes 2 seeded sequences and 2 KV heads."""
     wl = synth.config5(T, D, with_logits=False)
