@@ -201,33 +201,48 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(AttnParams p) {
 // ----------------------------------------------------------------------------------------------
 // Combine: grid (T_max, Hq, B), D threads.  out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
 // ----------------------------------------------------------------------------------------------
-template <typename T, int D>
-__global__ void __launch_bounds__(D) attn_combine_kernel(AttnParams p) {
-    const int k = blockIdx.x, h = blockIdx.y, b = blockIdx.z, c = threadIdx.x;
+// WPR wavefronts per query row (b, k, h), 4 / WPR rows per workgroup; a lane owns D / (64 * WPR) consecutive output
+// elements (two wavefronts per row for small launches, where the latency of a row's chain is what counts).
+// One pass over the splits in batches of eight (only splits that exist are read; a batch's loads are all in flight
+// together), with a running (M, L, acc) that is rescaled when a later batch raises the maximum.
+template <typename T, int D, int WPR>
+__global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
+    constexpr int E = D / (64 * WPR);
+    static_assert(E >= 1, "at least one element per lane");
+    const int wv = threadIdx.x >> 6;
+    const long row = (long)blockIdx.x * (4 / WPR) + wv / WPR;
+    const int lane = (wv % WPR) * 64 + (threadIdx.x & 63);  // position within the row, in units of E elements
+    const long rows_total = (long)p.B * p.T_max * p.Hq;
+    if (row >= rows_total) return;
+    const int h = (int)(row % p.Hq);
+    const long bk = row / p.Hq;
+    const int k = (int)(bk % p.T_max), b = (int)(bk / p.T_max);
     const int n = clampi(p.n_nodes[b], 0, p.T_max);
     T *out = static_cast<T *>(p.out);
-    const size_t orow = (((size_t)b * p.T_max + k) * p.Hq + h) * D;
+    const size_t orow = (((size_t)b * p.T_max + k) * p.Hq + h) * D + (size_t)lane * E;
     const size_t lrow = ((size_t)b * p.Hq + h) * p.T_max + k;
     if (k >= n) {
-        store_elem<T>(out, orow + c, 0.f);
-        if (p.lse && c == 0) p.lse[lrow] = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < E; e++) store_elem<T>(out, orow + e, 0.f);
+        if (p.lse && lane == 0) p.lse[lrow] = -INFINITY;
         return;
     }
     const int nvalid = seq_nsplit(p, seq_prefix_len(p, b));
     const size_t pr0 = part_row(p, b, 0, h, k);
     const size_t sstride = (size_t)p.Hq * p.T_max;  // rows between consecutive splits
-    // One pass: batches of eight splits, all of a batch's loads (m, l, O) in flight together, and a running
-    // (M, L, acc) that is rescaled when a later batch raises the maximum.
-    float M = -INFINITY, L = 0.f, acc = 0.f;
+    float M = -INFINITY, L = 0.f, acc[E];
+#pragma unroll
+    for (int e = 0; e < E; e++) acc[e] = 0.f;
     for (int s0 = 0; s0 < nvalid; s0 += 8) {
-        float ms[8], ls[8], os[8];
+        float ms[8], ls[8], os[8][E];
 #pragma unroll
         for (int u = 0; u < 8; u++) {
             const bool ok = s0 + u < nvalid;
             const size_t r = pr0 + (size_t)(ok ? s0 + u : 0) * sstride;
             ms[u] = ok ? p.part_m[r] : -INFINITY;
-            ls[u] = p.part_l[r];
-            os[u] = p.part_o[r * D + c];
+            ls[u] = ok ? p.part_l[r] : 0.f;
+#pragma unroll
+            for (int e = 0; e < E; e++) os[u][e] = ok ? p.part_o[r * D + (size_t)lane * E + e] : 0.f;
         }
         float Mb = M;
 #pragma unroll
@@ -235,19 +250,22 @@ __global__ void __launch_bounds__(D) attn_combine_kernel(AttnParams p) {
         if (Mb == -INFINITY) continue;  // nothing visible in this batch or before
         const float keep = exp2f(M - Mb);  // 0 while M is still -inf
         L *= keep;
-        acc *= keep;
+#pragma unroll
+        for (int e = 0; e < E; e++) acc[e] *= keep;
         M = Mb;
 #pragma unroll
         for (int u = 0; u < 8; u++) {
             if (ms[u] != -INFINITY) {  // absent or empty split: its l/O may be uninitialised memory
                 const float w = exp2f(ms[u] - M);
                 L = fmaf(w, ls[u], L);
-                acc = fmaf(w, os[u], acc);
+#pragma unroll
+                for (int e = 0; e < E; e++) acc[e] = fmaf(w, os[u][e], acc[e]);
             }
         }
     }
-    store_elem<T>(out, orow + c, acc / L);
-    if (p.lse && c == 0) p.lse[lrow] = (M + log2f(L)) * kLn2;
+#pragma unroll
+    for (int e = 0; e < E; e++) store_elem<T>(out, orow + e, acc[e] / L);
+    if (p.lse && lane == 0) p.lse[lrow] = (M + log2f(L)) * kLn2;
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -634,12 +652,17 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     uint8_t *const smem = attn_smem;
     const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)attn_smem;
 
-    const int s = blockIdx.x;
     // Row groups (wg) of one KV head read the same K/V.  Workgroups go to the 8 XCDs round-robin by linear id;
     // with wg as the slow index the ids of one (split, KV head) differ by multiples of nsplit * Hkv, i.e. (for
     // Hkv a multiple of 8) they share an XCD and the second reader of a K/V line finds it in that XCD's L2.
     const int wg = blockIdx.y / p.Hkv, kvh = blockIdx.y % p.Hkv;
     const int b = blockIdx.z;
+    // The split index is rotated by the sequence index.  Unrotated, split s of every sequence lands on XCD s
+    // (mod 8 with the head): in a ragged batch the first splits are all full and the last ones short or absent,
+    // so some XCDs carry all the long workgroups and finish half as late again as the others.  (Not rotated by
+    // the KV head: in a contiguous cache the heads of a key row are neighbours in memory, and the XCD that
+    // reads one of them should read all of them at about the same time.)
+    const int s = (int)((blockIdx.x + blockIdx.z) % p.nsplit);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c32 = lane & 31, hh = lane >> 5;
@@ -1112,14 +1135,20 @@ extern "C" int32_t etv_tree_verify_attention(const etv_attn_desc *h, const void 
         rc = check_launch();
     }
     if (rc != ETV_OK || pl.nsplit == 1) return rc;
-    dim3 cgrid(h->T_max, h->Hq, h->B);
+    const long crows = (long)h->B * h->T_max * h->Hq;
+    const bool two = h->d == 128 && crows <= 512;  // very few rows: two wavefronts per row
+    dim3 cgrid((unsigned)((crows + (two ? 1 : 3)) / (two ? 2 : 4)));
     if (h->dtype == ETV_F32 && h->d == 64)
-        hipLaunchKernelGGL((attn_combine_kernel<float, 64>), cgrid, dim3(64), 0, st, p);
+        hipLaunchKernelGGL((attn_combine_kernel<float, 64, 1>), cgrid, dim3(256), 0, st, p);
+    else if (h->dtype == ETV_F32 && two)
+        hipLaunchKernelGGL((attn_combine_kernel<float, 128, 2>), cgrid, dim3(256), 0, st, p);
     else if (h->dtype == ETV_F32)
-        hipLaunchKernelGGL((attn_combine_kernel<float, 128>), cgrid, dim3(128), 0, st, p);
+        hipLaunchKernelGGL((attn_combine_kernel<float, 128, 1>), cgrid, dim3(256), 0, st, p);
     else if (h->d == 64)
-        hipLaunchKernelGGL((attn_combine_kernel<uint16_t, 64>), cgrid, dim3(64), 0, st, p);
+        hipLaunchKernelGGL((attn_combine_kernel<uint16_t, 64, 1>), cgrid, dim3(256), 0, st, p);
+    else if (two)
+        hipLaunchKernelGGL((attn_combine_kernel<uint16_t, 128, 2>), cgrid, dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL((attn_combine_kernel<uint16_t, 128>), cgrid, dim3(128), 0, st, p);
+        hipLaunchKernelGGL((attn_combine_kernel<uint16_t, 128, 1>), cgrid, dim3(256), 0, st, p);
     return check_launch();
 }
