@@ -129,10 +129,23 @@ __global__ void __launch_bounds__(ETV_MAX_TREE) build_tree_mask_kernel(
     if (k == 0) status[b] = s_status;
     if (dense) {
         uint8_t *out = dense + (size_t)b * T_max * T_max;
-        const int total = T_max * T_max;
-        for (int e = k; e < total; e += blockDim.x) {
-            int row = e / T_max, col = e - row * T_max;
-            out[e] = (uint8_t)((s_bits[row][col >> 6] >> (col & 63)) & 1ull);
+        if ((T_max & 3) == 0 && (((uintptr_t)dense) & 3) == 0) {
+            // four mask bytes per store: thread k keeps one 4-byte group of a row and walks down the rows
+            // (groups = T_max / 4 <= 64 <= blockDim: one division per thread, none per element)
+            const int groups = T_max >> 2;
+            const int g = k % groups, rstep = blockDim.x / groups;
+            uint32_t *out4 = reinterpret_cast<uint32_t *>(out);
+            for (int row = k / groups; row < T_max && k < rstep * groups; row += rstep) {
+                const uint32_t nib = (uint32_t)(s_bits[row][g >> 4] >> ((g & 15) * 4)) & 15u;
+                // bit i of the nibble -> byte i
+                out4[row * groups + g] = (nib & 1u) | ((nib & 2u) << 7) | ((nib & 4u) << 14) | ((nib & 8u) << 21);
+            }
+        } else {
+            const int total = T_max * T_max;
+            for (int e = k; e < total; e += blockDim.x) {
+                int row = e / T_max, col = e - row * T_max;
+                out[e] = (uint8_t)((s_bits[row][col >> 6] >> (col & 63)) & 1ull);
+            }
         }
     }
 }
