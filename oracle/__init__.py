@@ -165,12 +165,18 @@ def evaluate_posterior(logits, tokens, retrieve, n_nodes, dummy: int = 0):
 
 
 def commit_accepted_kv(kt, vt, k_cache, v_cache, prefix_len, capacity, n_nodes, acc_nodes, accept_len, *,
-                       block_table=None):
+                       block_table=None, T_max=None):
     """kt/vt [Lyr,B,T,Hkv,d]; caches [Lyr, ...] (contiguous [B,P_cap,Hkv,d] or paged [nb,Hkv,bs,d]).
+    kt = vt = None (with T_max): the tree rows sit in the cache itself at positions prefix_len + node.
     Caches are updated IN PLACE; returns prefix_len_out, slot_map, status."""
-    Lyr, B, T, Hkv, d = kt.shape
-    assert k_cache.shape[0] == Lyr and k_cache.flags["C_CONTIGUOUS"] and v_cache.flags["C_CONTIGUOUS"]
-    eb = kt.dtype.itemsize
+    assert k_cache.flags["C_CONTIGUOUS"] and v_cache.flags["C_CONTIGUOUS"]
+    if kt is not None:
+        Lyr, B, T, Hkv, d = kt.shape
+        eb = kt.dtype.itemsize
+    else:
+        Lyr, B, T, eb = k_cache.shape[0], len(prefix_len), int(T_max), k_cache.dtype.itemsize
+        Hkv, d = (k_cache.shape[2], k_cache.shape[4]) if block_table is not None else (k_cache.shape[3], k_cache.shape[4])
+    assert k_cache.shape[0] == Lyr
     layer_stride = int(np.prod(k_cache.shape[1:]))
     if block_table is not None:
         block_table = _i32(block_table)

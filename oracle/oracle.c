@@ -455,6 +455,13 @@ int orc_evaluate_posterior(const float *logits, const int32_t *tokens, const int
  *
  * Layouts: kt, vt [n_layers,B,T_max,Hkv,d]; caches as in attention with a
  * leading layer axis of cache_layer_stride elements.
+ *
+ * In-place branch cache (kt == vt == NULL), Section 3.3 "KV-cache writes and
+ * commit": the verification pass has extended the cache in place, so the tree
+ * row of node j already sits at logical position P + j of the cache itself,
+ * and the same gather by path_indices is taken over the cache alone (from a
+ * snapshot, so no row is read after it has been overwritten).  The tail must
+ * fit: P + n_nodes > capacity is a CAPACITY failure.
  * ---------------------------------------------------------------------- */
 int orc_commit_accepted_kv(int B, int T_max, int Hkv, int d, int elem_bytes, int n_layers, const void *kt,
                            const void *vt, void *k_cache, void *v_cache, size_t cache_layer_stride,
@@ -474,8 +481,9 @@ int orc_commit_accepted_kv(int B, int T_max, int Hkv, int d, int elem_bytes, int
                 if (nd < 0 || nd >= n) st |= ORC_COMMIT_BAD_NODE;
             }
             if ((long)P + A + 1 > (long)capacity[b]) st |= ORC_COMMIT_CAPACITY;
+            if (!kt && (long)P + n > (long)capacity[b]) st |= ORC_COMMIT_CAPACITY;
             if (!(st & ORC_COMMIT_CAPACITY) && block_table)
-                for (int i = 0; i <= A; i++) {
+                for (int i = 0; i < (kt ? A + 1 : (n > A + 1 ? n : A + 1)); i++) {
                     int pos = P + i;
                     if (pos / block_size >= max_blocks) {
                         st |= ORC_COMMIT_CAPACITY;
@@ -493,7 +501,8 @@ int orc_commit_accepted_kv(int B, int T_max, int Hkv, int d, int elem_bytes, int
         }
         size_t newlen = (size_t)P + A + 1;
         size_t *path_idx = (size_t *)malloc(sizeof(size_t) * newlen);
-        char *cat = (char *)malloc(((size_t)P + T_max) * rowb);
+        const size_t catlen = (size_t)P + (kt ? (size_t)T_max : (size_t)n); /* branch cache length */
+        char *cat = (char *)malloc(catlen * rowb);
         char *neu = (char *)malloc(newlen * rowb);
         if (!path_idx || !cat || !neu) return ORC_ERR_NOMEM;
         for (int j = 0; j < P; j++) path_idx[j] = (size_t)j;
@@ -503,10 +512,10 @@ int orc_commit_accepted_kv(int B, int T_max, int Hkv, int d, int elem_bytes, int
                 for (int hh = 0; hh < Hkv; hh++) {
                     char *cache = (char *)(kv ? v_cache : k_cache) + (size_t)l * cache_layer_stride * elem_bytes;
                     const char *tree = (const char *)(kv ? vt : kt);
-                    /* branch cache of this (layer, head): prefix rows then tree rows */
-                    for (size_t j = 0; j < (size_t)P + T_max; j++) {
+                    /* branch cache of this (layer, head): prefix rows then tree rows (in place: the cache tail) */
+                    for (size_t j = 0; j < catlen; j++) {
                         const char *srcp;
-                        if (j < (size_t)P) {
+                        if (j < (size_t)P || !tree) {
                             size_t off;
                             if (block_table) {
                                 int blk = block_table[(size_t)b * max_blocks + j / block_size];

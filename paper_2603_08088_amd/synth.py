@@ -277,8 +277,11 @@ def _values(rng: np.random.Generator, shape, dtype: str, scale: float = 1.0) -> 
 def assemble(name: str, rng: np.random.Generator, parents: List[np.ndarray], prefix_lens: List[int], *,
              Hq: int, Hkv: int, d: int, dtype: str, V: int, W: int, paged: bool,
              T_max: Optional[int] = None, spare_blocks: int = 64, want_depths: Optional[List[int]] = None,
-             with_logits: bool = True, q_scale: float = 1.0, with_cache: bool = True) -> Workload:
-    """Pack per-sequence trees into padded batch arrays and draw all values."""
+             with_logits: bool = True, q_scale: float = 1.0, with_cache: bool = True,
+             tail_room: int = 0) -> Workload:
+    """Pack per-sequence trees into padded batch arrays and draw all values.  The cache has room for W more
+    positions behind every prefix (the longest accepted path), or for tail_room if that is larger (a branch
+    cache that holds the whole tree in place)."""
     B = len(parents)
     T_max = T_max or max(len(p) for p in parents)
     wl = Workload(name=name, B=B, T_max=T_max, Hq=Hq, Hkv=Hkv, d=d, dtype=dtype, V=V, W=W, paged=paged)
@@ -298,7 +301,7 @@ def assemble(name: str, rng: np.random.Generator, parents: List[np.ndarray], pre
     wl.kt = _values(rng, (B, T_max, Hkv, d), dtype)
     wl.vt = _values(rng, (B, T_max, Hkv, d), dtype)
     if paged:
-        need = [(int(P) + W + BLOCK - 1) // BLOCK for P in prefix_lens]
+        need = [(int(P) + max(W, tail_room) + BLOCK - 1) // BLOCK for P in prefix_lens]
         wl.max_blocks = max(need)
         wl.num_blocks = sum(need) + spare_blocks
         perm = rng.permutation(wl.num_blocks).astype(np.int32)
@@ -312,7 +315,7 @@ def assemble(name: str, rng: np.random.Generator, parents: List[np.ndarray], pre
             wl.k_cache = _values(rng, (wl.num_blocks, Hkv, BLOCK, d), dtype)
             wl.v_cache = _values(rng, (wl.num_blocks, Hkv, BLOCK, d), dtype)
     else:
-        wl.P_cap = max(int(P) for P in prefix_lens) + W
+        wl.P_cap = max(int(P) for P in prefix_lens) + max(W, tail_room)
         wl.capacity = np.full(B, wl.P_cap, dtype=np.int32)
         if with_cache:
             wl.k_cache = _values(rng, (B, wl.P_cap, Hkv, d), dtype)

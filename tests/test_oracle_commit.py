@@ -119,3 +119,77 @@ def test_accept_zero_commits_exactly_the_root_and_failures_leave_the_cache_untou
     r = oracle.commit_accepted_kv(kt, vt, kc, vc, wl.prefix_len, wl.capacity, wl.n_nodes, acc, [0, 9, -1],
                                   block_table=wl.block_table)
     assert r["status"].tolist() == [0, oracle.COMMIT_BAD_LEN, oracle.COMMIT_BAD_LEN]
+
+
+def _tail_workload(rng, B, T, P, paged, Lyr=2, dtype="bf16"):
+    """A workload whose cache already holds the tree rows in place: node j of sequence b at position P_b + j."""
+    parents = [random_tree(rng, T) for _ in range(B)]
+    wl = synth.assemble("t", rng, parents, P, Hq=2, Hkv=2, d=8, dtype=dtype, V=512, W=T, paged=paged,
+                        with_logits=False, spare_blocks=5, tail_room=T)
+    kt = np.stack([wl.kt] + [synth._values(rng, wl.kt.shape, dtype) for _ in range(Lyr - 1)])
+    vt = np.stack([wl.vt] + [synth._values(rng, wl.vt.shape, dtype) for _ in range(Lyr - 1)])
+    kc = np.stack([wl.k_cache] + [synth._values(rng, wl.k_cache.shape, dtype) for _ in range(Lyr - 1)])
+    vc = np.stack([wl.v_cache] + [synth._values(rng, wl.v_cache.shape, dtype) for _ in range(Lyr - 1)])
+    for b in range(B):
+        for j in range(int(wl.n_nodes[b])):
+            pos = int(wl.prefix_len[b]) + j
+            if paged:
+                blk, off = wl.block_table[b, pos // synth.BLOCK], pos % synth.BLOCK
+                kc[:, blk, :, off] = kt[:, b, j]
+                vc[:, blk, :, off] = vt[:, b, j]
+            else:
+                kc[:, b, pos] = kt[:, b, j]
+                vc[:, b, pos] = vt[:, b, j]
+    return wl, kt, vt, kc, vc
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_in_place_branch_cache_commit_equals_the_separate_buffer_commit_on_the_committed_rows(paged):
+    """With the tree rows already in the cache tail, compaction must leave positions 0..P+A exactly as the commit
+    from a separate tree buffer does (which is pinned to sequential appends above), including the hazardous
+    cases where a destination P+i is the tail position of a node accepted earlier."""
+    rng = np.random.default_rng(35)
+    B, T = 5, 12
+    wl, kt, vt, kc, vc = _tail_workload(rng, B, T, [20, 16, 15, 33, 7], paged)
+    acc = np.zeros((B, T), dtype=np.int32)
+    A = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        path = wl.retrieve[b, b % wl.n_paths[b]]
+        plen = int((path >= 0).sum())
+        A[b] = plen - 1
+        acc[b, :plen] = path[:plen]
+    kc_ref, vc_ref = kc.copy(), vc.copy()
+    r_ref = oracle.commit_accepted_kv(kt, vt, kc_ref, vc_ref, wl.prefix_len, wl.capacity, wl.n_nodes, acc, A,
+                                      block_table=wl.block_table)
+    r = oracle.commit_accepted_kv(None, None, kc, vc, wl.prefix_len, wl.capacity, wl.n_nodes, acc, A,
+                                  block_table=wl.block_table, T_max=T)
+    assert np.all(r["status"] == 0) and np.all(r_ref["status"] == 0)
+    for key in r:
+        assert np.array_equal(r[key], r_ref[key]), key
+    hazard = False
+    for b in range(B):
+        P = int(wl.prefix_len[b])
+        for i in range(int(A[b]) + 1):
+            hazard |= any(int(acc[b, j]) == i for j in range(i))      # destination i was the source of an earlier j
+            pos = P + i
+            if paged:
+                blk, off = wl.block_table[b, pos // synth.BLOCK], pos % synth.BLOCK
+                assert np.array_equal(kc[:, blk, :, off], kc_ref[:, blk, :, off])
+                assert np.array_equal(vc[:, blk, :, off], vc_ref[:, blk, :, off])
+                assert np.array_equal(kc[:, blk, :, off], kt[:, b, acc[b, i]])
+            else:
+                assert np.array_equal(kc[:, b, pos], kc_ref[:, b, pos]) and np.array_equal(vc[:, b, pos], vc_ref[:, b, pos])
+                assert np.array_equal(kc[:, b, pos], kt[:, b, acc[b, i]])
+    assert hazard, "the seeded trees must include an accepted node whose tail slot is overwritten later"
+
+
+def test_in_place_commit_needs_room_for_the_tail():
+    rng = np.random.default_rng(36)
+    wl, kt, vt, kc, vc = _tail_workload(rng, 2, 9, [10, 12], False)
+    before = kc.copy()
+    cap = wl.capacity.copy()
+    cap[1] = wl.prefix_len[1] + 5                 # room for the accepted path but not for the 9-node tail
+    acc = np.zeros((2, 9), dtype=np.int32)
+    r = oracle.commit_accepted_kv(None, None, kc, vc, wl.prefix_len, cap, wl.n_nodes, acc, [0, 0], T_max=9)
+    assert r["status"].tolist() == [0, 1] and int(r["prefix_len_out"][1]) == 12
+    assert np.array_equal(kc[:, 1], before[:, 1])
