@@ -138,7 +138,10 @@ ETV_API int32_t etv_tensorize_tree(const int32_t *parent, const int32_t *n_nodes
  *
  * Layouts (row-major, innermost last; element type per h_desc->dtype):
  *  q, out        [B, T_max, Hq, d]
- *  kt, vt        [B, T_max, Hkv, d]                    K/V of the tree tokens of this step
+ *  kt, vt        [B, T_max, Hkv, d]                    K/V of the tree tokens of this step; both NULL: an
+ *                in-place branch cache (Section 3.3 "KV-cache writes and commit") -- the verification pass has
+ *                written the K/V of node j of sequence b into the cache itself at position prefix_len[b] + j
+ *                (so P_max + T_max positions must exist: P_cap, or max_blocks * block_size when paged)
  *  k_cache/v_cache  contiguous (block_size == 0): [B, P_cap, Hkv, d]
  *                   paged (block_size == 16):     [num_blocks, Hkv, block_size, d], logical position p of
  *                   sequence b lives in block block_table[b][p / block_size] at offset p % block_size
@@ -235,7 +238,10 @@ ETV_API int32_t etv_evaluate_posterior(const float *logits, const int32_t *token
  * A sequence that fails a check is left untouched (status bit set, prefix_len_out
  * = prefix_len, slot_map = -1).
  *
- *  kt, vt       [n_layers, B, T_max, Hkv, d]
+ *  kt, vt       [n_layers, B, T_max, Hkv, d]; both NULL: in-place branch cache -- the tree rows are in the cache
+ *               at positions prefix_len[b] + node, and the accepted ones are compacted to prefix_len[b] + i
+ *               (path-index commit over the cache alone; needs prefix_len[b] + n_nodes[b] <= capacity[b], else
+ *               ETV_COMMIT_CAPACITY; prefix_len_out must not alias prefix_len)
  *  k_cache/v_cache: layer l starts cache_layer_stride elements after layer l-1; per-layer layout as in attention
  *  prefix_len, capacity, n_nodes, accept_len int32 [B]; acc_nodes int32 [B, W]
  *  prefix_len_out int32 [B] (may alias prefix_len); slot_map int32 [B, W]; status int32 [B]

@@ -181,7 +181,8 @@ def tensorize_tree(parent: torch.Tensor, n_nodes: torch.Tensor, prefix_len: torc
 def attn_desc(q: torch.Tensor, kt: torch.Tensor, k_cache: Optional[torch.Tensor], block_table: Optional[torch.Tensor],
               P_max: int, scale: float = 0.0, kv_split: int = 0, flags: int = 0) -> AttnDesc:
     B, T, Hq, d = q.shape
-    Hkv = kt.shape[2]
+    # kt None: in-place branch cache, the tree rows are in k_cache / v_cache behind the prefix
+    Hkv = kt.shape[2] if kt is not None else (k_cache.shape[1] if block_table is not None else k_cache.shape[2])
     dsc = AttnDesc(B=B, T_max=T, Hq=Hq, Hkv=Hkv, d=d, dtype=_dtype_code(q), block_size=0, max_blocks=0,
                    num_blocks=0, P_cap=0, P_max=int(P_max), scale=float(scale), kv_split=int(kv_split),
                    flags=int(flags))
@@ -309,10 +310,14 @@ def lm_head_argmax(hidden, weight, n_nodes, *, V: Optional[int] = None, want_max
     return dict(argmax=g, maxval=mx) if finish else dict(workspace=workspace)
 
 
-def _commit_desc(kt, k_cache, block_table, W: int) -> CommitDesc:
-    Lyr, B, T, Hkv, d = kt.shape
+def _commit_desc(kt, k_cache, block_table, W: int, B: Optional[int] = None, T_max: Optional[int] = None) -> CommitDesc:
+    if kt is not None:
+        Lyr, B, T, Hkv, d = kt.shape
+    else:   # in-place branch cache: shapes from the cache, B and T_max from the caller
+        Lyr, T = k_cache.shape[0], int(T_max)
+        Hkv, d = (k_cache.shape[2], k_cache.shape[4]) if block_table is not None else (k_cache.shape[3], k_cache.shape[4])
     assert k_cache.shape[0] == Lyr
-    dsc = CommitDesc(B=B, T_max=T, Hkv=Hkv, d=d, elem_bytes=kt.element_size(), n_layers=Lyr, W=W, block_size=0,
+    dsc = CommitDesc(B=B, T_max=T, Hkv=Hkv, d=d, elem_bytes=k_cache.element_size(), n_layers=Lyr, W=W, block_size=0,
                      max_blocks=0, num_blocks=0, P_cap=0, reserved=0,
                      cache_layer_stride=k_cache.stride(0) if Lyr > 1 else k_cache[0].numel())
     if block_table is not None:
@@ -353,7 +358,7 @@ def verify_epilogue(logits, tokens, retrieve, n_nodes, kt, vt, k_cache, v_cache,
     plo, slot, status = get(co, "prefix_len_out", (B,)), get(co, "slot_map", (B, W)), get(co, "status", (B,))
     if workspace is None and logits is not None:
         workspace = torch.empty((max(256, evaluate_posterior_workspace_bytes(B, T, V)),), dtype=torch.uint8, device=dev)
-    dsc = _commit_desc(kt, k_cache, block_table, W)
+    dsc = _commit_desc(kt, k_cache, block_table, W, B, T)
     rc = lib().etv_verify_epilogue(C.byref(dsc), _ptr(logits), V, _ptr(tokens), _ptr(retrieve), L, dummy, _ptr(src),
                                    row_bytes, _ptr(safe), _ptr(pvalid), _ptr(gathered), _ptr(g), _ptr(ln), _ptr(best),
                                    _ptr(A), _ptr(acc), _ptr(bonus), _ptr(kt), _ptr(vt), _ptr(k_cache), _ptr(v_cache),
@@ -367,20 +372,14 @@ def verify_epilogue(logits, tokens, retrieve, n_nodes, kt, vt, k_cache, v_cache,
 
 
 def commit_accepted_kv(kt, vt, k_cache, v_cache, prefix_len, capacity, n_nodes, acc_nodes, accept_len, *,
-                       block_table=None, prefix_len_out=None, out: Optional[Dict[str, torch.Tensor]] = None):
+                       block_table=None, prefix_len_out=None, out: Optional[Dict[str, torch.Tensor]] = None,
+                       T_max: Optional[int] = None):
     """kt/vt [Lyr,B,T,Hkv,d]; caches [Lyr,B,P_cap,Hkv,d] or [Lyr,nb,Hkv,bs,d] updated in place.
+    kt = vt = None (with T_max): in-place branch cache, the tree rows are in the caches behind the prefix.
     Returns prefix_len_out, slot_map, status."""
-    Lyr, B, T, Hkv, d = kt.shape
-    assert k_cache.shape[0] == Lyr
-    W = acc_nodes.shape[1]
-    dev = kt.device
-    dsc = CommitDesc(B=B, T_max=T, Hkv=Hkv, d=d, elem_bytes=kt.element_size(), n_layers=Lyr, W=W, block_size=0,
-                     max_blocks=0, num_blocks=0, P_cap=0, reserved=0,
-                     cache_layer_stride=k_cache.stride(0) if Lyr > 1 else k_cache[0].numel())
-    if block_table is not None:
-        dsc.block_size, dsc.max_blocks, dsc.num_blocks = k_cache.shape[3], block_table.shape[1], k_cache.shape[1]
-    else:
-        dsc.P_cap = k_cache.shape[2]
+    B, W = acc_nodes.shape
+    dev = k_cache.device
+    dsc = _commit_desc(kt, k_cache, block_table, W, B, T_max)
     o = out or {}
     if prefix_len_out is None:
         prefix_len_out = o.get("prefix_len_out")

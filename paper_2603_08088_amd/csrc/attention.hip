@@ -178,8 +178,13 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(AttnParams p) {
             const int j = t0 + lane;
             const bool valid = (j < n) && ((mrow[t0 >> 6] >> lane) & 1ull);
             float sc = 0.f;
-            if (valid) sc = dot_row<T, D>(sq, kt + tree_row_offset(p, b, kvh, j)) * p.scale_log2;
-            tile(sc, valid, min(64, n - t0), [&](int jj) { return vt + tree_row_offset(p, b, kvh, t0 + jj); });
+            // tree rows: the step's own buffer, or (kt null) the cache tail, node j at position P + j
+            if (valid)
+                sc = (kt ? dot_row<T, D>(sq, kt + tree_row_offset(p, b, kvh, j))
+                         : dot_row<T, D>(sq, kc + prefix_row_offset(p, b, kvh, P + j))) * p.scale_log2;
+            tile(sc, valid, min(64, n - t0), [&](int jj) {
+                return kt ? vt + tree_row_offset(p, b, kvh, t0 + jj) : vc + prefix_row_offset(p, b, kvh, P + t0 + jj);
+            });
         }
     }
     if (direct) {
@@ -374,6 +379,8 @@ struct TileLoader {
     size_t row_stride, seq_off, blk_stride, head_off;  // strides are below 2^32
     uint32_t smem_addr;
     int wave, l_row, l_pos, k0, k1, npt, n;
+    int P;      // prefix length of the sequence
+    bool tail;  // the tree rows live in the cache itself, node j at position P + j (no separate tree buffer)
     uint32_t kcol, vcol;  // per-lane source column (bytes) for the K tile / the V tile swizzle
     uint32_t koff, voff;  // per-lane byte offset from the scalar base of a chunk pair (full tiles)
 };
@@ -417,16 +424,23 @@ __device__ __forceinline__ void issue_edge_tile(const TileLoader<NW> &ld, int ti
     const int base = tree ? (ti - ld.npt) * KT : ld.k0 + ti * KT;
     const int last = (tree ? ld.n : ld.k1) - 1;
     const uint32_t stage = ld.smem_addr + (uint32_t)(ti % NS) * STAGE_BYTES;
-    const uint8_t *ksrc = tree ? ld.kt : ld.kc;
-    const uint8_t *vsrc = tree ? ld.vt : ld.vc;
+    const bool own = tree && !ld.tail;  // rows of the step's own tree buffer
+    const uint8_t *ksrc = own ? ld.kt : ld.kc;
+    const uint8_t *vsrc = own ? ld.vt : ld.vc;
 #pragma unroll
     for (int u = 0; u < U; u++) {
         const int j = ld.wave + NI * u;
         const int r_in = 4 * j + ld.l_row;
         const int key = min(base + r_in, last);
         size_t off;
-        if (tree) {
+        if (own) {
             off = (size_t)key * ld.row_stride;
+        } else if (tree) {
+            // in-place branch cache: node `key` sits at cache position P + key.  P is arbitrary, so the four rows
+            // of a chunk may lie in two blocks: the block id is looked up per lane.
+            const int pos = ld.P + key;
+            if (ld.bt) off = (size_t)ld.bt[pos >> 4] * ld.blk_stride + ld.head_off + (size_t)(pos & 15) * ROW_BYTES;
+            else off = ld.seq_off + (size_t)pos * ld.row_stride;
         } else if (ld.bt) {
             // the logical block is the same for the whole chunk (its rows are clamped into one block)
             const int lb = __builtin_amdgcn_readfirstlane(min(base + 4 * j, last) >> 4);
@@ -745,7 +759,7 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     ld.head_off = (size_t)kvh * 16 * ROW_BYTES;
     ld.kf = ld.kc + (PAGED ? ld.head_off : ld.seq_off); ld.vf = ld.vc + (PAGED ? ld.head_off : ld.seq_off);
     ld.smem_addr = smem_addr; ld.wave = wave; ld.l_row = lane >> 4; ld.l_pos = lane & 15;
-    ld.k0 = k0; ld.k1 = k1; ld.npt = npt; ld.n = n;
+    ld.k0 = k0; ld.k1 = k1; ld.npt = npt; ld.n = n; ld.P = P; ld.tail = (p.kt == nullptr);
     {
         // the lane's row within the 16 rows that pair `wave` + 4u covers, the same for every u
         const int r_in = 4 * wave + ld.l_row;
@@ -1059,7 +1073,9 @@ extern "C" int32_t etv_tree_verify_attention(const etv_attn_desc *h, const void 
                                              const uint64_t *bitmask, const int32_t *n_nodes, void *out, float *lse,
                                              void *workspace, size_t workspace_bytes, void *stream) {
     using namespace etv;
-    if (!h || !q || !prefix_len || !kt || !vt || !bitmask || !n_nodes || !out) return ETV_ERR_INVALID_ARG;
+    if (!h || !q || !prefix_len || !bitmask || !n_nodes || !out) return ETV_ERR_INVALID_ARG;
+    if ((kt == nullptr) != (vt == nullptr)) return ETV_ERR_INVALID_ARG;
+    const bool tail = (kt == nullptr);  // in-place branch cache: the tree rows are in the cache behind the prefix
     if (!supported(h)) return ETV_ERR_INVALID_ARG;
     if (h->Hq % h->Hkv != 0) return ETV_ERR_INVALID_ARG;
     if (h->dtype != ETV_F32 && h->dtype != ETV_BF16) return ETV_ERR_UNSUPPORTED;
@@ -1068,9 +1084,10 @@ extern "C" int32_t etv_tree_verify_attention(const etv_attn_desc *h, const void 
     if (h->P_max < 0) return ETV_ERR_INVALID_ARG;
     if (h->block_size != 0 && h->block_size != 16) return ETV_ERR_UNSUPPORTED;
     if (h->block_size > 0 && (!block_table || h->max_blocks < 1)) return ETV_ERR_INVALID_ARG;
-    if (h->block_size > 0 && (long)h->P_max > (long)h->max_blocks * h->block_size) return ETV_ERR_INVALID_ARG;
-    if (h->block_size == 0 && h->P_max > h->P_cap) return ETV_ERR_INVALID_ARG;
-    if (h->P_max > 0 && (!k_cache || !v_cache)) return ETV_ERR_INVALID_ARG;
+    const long reach = (long)h->P_max + (tail ? h->T_max : 0);  // cache positions the kernel may read
+    if (h->block_size > 0 && reach > (long)h->max_blocks * h->block_size) return ETV_ERR_INVALID_ARG;
+    if (h->block_size == 0 && reach > h->P_cap) return ETV_ERR_INVALID_ARG;
+    if (reach > 0 && (!k_cache || !v_cache)) return ETV_ERR_INVALID_ARG;
     if (h->kv_split < 0) return ETV_ERR_INVALID_ARG;
     const uintptr_t align = (uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)kt | (uintptr_t)vt |
                             (uintptr_t)out | (uintptr_t)workspace;

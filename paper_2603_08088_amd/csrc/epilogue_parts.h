@@ -152,11 +152,13 @@ __device__ __forceinline__ void posterior_for_sequence(
 // Commit plan of sequence b by one thread: validate, physical slot of every appended position, new prefix
 // length.  acc_row: the W accepted node rows of the sequence.  Section 3.1 "Commit by path indices and
 // prefix-sharing fast reorder".
+// in_place: the tree rows are in the cache tail (positions P .. P + n - 1), which must then exist as well.
 __device__ __forceinline__ void commit_plan_for_sequence(const etv_commit_desc &dsc, int b,
                                                          const int32_t *__restrict__ block_table, int P, int cap,
                                                          int n, const int32_t *acc_row, int A,
                                                          int32_t *__restrict__ prefix_len_out,
-                                                         int32_t *__restrict__ slot_map, int32_t *__restrict__ status) {
+                                                         int32_t *__restrict__ slot_map, int32_t *__restrict__ status,
+                                                         bool in_place = false) {
     const int W = dsc.W;
     int32_t st = 0;
     if (A < 0 || A > W - 1) st |= ETV_COMMIT_BAD_LEN;
@@ -166,8 +168,10 @@ __device__ __forceinline__ void commit_plan_for_sequence(const etv_commit_desc &
             if (nd < 0 || nd >= n) st |= ETV_COMMIT_BAD_NODE;
         }
         if ((long)P + A + 1 > (long)cap || P < 0) st |= ETV_COMMIT_CAPACITY;
+        if (in_place && (long)P + n > (long)cap) st |= ETV_COMMIT_CAPACITY;
+        const int reach = in_place ? max(n, A + 1) : A + 1;  // positions behind P that are read or written
         if (!(st & ETV_COMMIT_CAPACITY) && dsc.block_size > 0) {
-            for (int i = 0; i <= A; i++) {
+            for (int i = 0; i < reach; i++) {
                 int lb = (P + i) / dsc.block_size;
                 if (lb >= dsc.max_blocks) {
                     st |= ETV_COMMIT_CAPACITY;
@@ -176,7 +180,7 @@ __device__ __forceinline__ void commit_plan_for_sequence(const etv_commit_desc &
                 int blk = block_table[(size_t)b * dsc.max_blocks + lb];
                 if (blk < 0 || blk >= dsc.num_blocks) st |= ETV_COMMIT_BAD_BLOCK;
             }
-        } else if (!(st & ETV_COMMIT_CAPACITY) && (long)P + A + 1 > (long)dsc.P_cap) {
+        } else if (!(st & ETV_COMMIT_CAPACITY) && (long)P + reach > (long)dsc.P_cap) {
             st |= ETV_COMMIT_CAPACITY;
         }
     }
@@ -199,5 +203,8 @@ int32_t check_commit_args(const etv_commit_desc *h, const void *kt, const void *
                           const void *v_cache, const int32_t *block_table);
 int32_t launch_commit_copy(const etv_commit_desc *h, const void *kt, const void *vt, void *k_cache, void *v_cache,
                            const int32_t *acc_nodes, const int32_t *slot_map, hipStream_t s);
+int32_t launch_commit_compact(const etv_commit_desc *h, void *k_cache, void *v_cache, const int32_t *block_table,
+                              const int32_t *prefix_len, const int32_t *acc_nodes, const int32_t *accept_len,
+                              const int32_t *slot_map, hipStream_t s);
 
 }  // namespace etv

@@ -94,7 +94,8 @@ __global__ void __launch_bounds__(256) verify_epilogue_kernel(
     int32_t *__restrict__ len, int32_t *__restrict__ best, int32_t *__restrict__ accept_len,
     int32_t *__restrict__ acc_nodes, int32_t *__restrict__ bonus, const int32_t *__restrict__ block_table,
     const int32_t *__restrict__ prefix_len, const int32_t *__restrict__ capacity,
-    int32_t *__restrict__ prefix_len_out, int32_t *__restrict__ slot_map, int32_t *__restrict__ status) {
+    int32_t *__restrict__ prefix_len_out, int32_t *__restrict__ slot_map, int32_t *__restrict__ status,
+    int in_place) {
     __shared__ int32_t s_A;
     __shared__ int32_t s_acc[ETV_MAX_TREE];
     const int t = threadIdx.x;
@@ -114,7 +115,7 @@ __global__ void __launch_bounds__(256) verify_epilogue_kernel(
                            accept_len, acc_nodes, bonus, &s_A, s_acc);
     if (t == 0)
         commit_plan_for_sequence(dsc, b, block_table, prefix_len[b], capacity[b], n, s_acc, s_A, prefix_len_out,
-                                 slot_map, status);
+                                 slot_map, status, in_place != 0);
 }
 
 }  // namespace etv
@@ -201,6 +202,8 @@ extern "C" int32_t etv_verify_epilogue(const etv_commit_desc *h, const float *lo
     if ((src == nullptr) != (gathered == nullptr)) return ETV_ERR_INVALID_ARG;
     if (src && row_bytes == 0) return ETV_ERR_INVALID_ARG;
     if (h->T_max > ETV_MAX_TREE || h->W > ETV_MAX_TREE) return ETV_ERR_UNSUPPORTED;
+    const bool in_place = (kt == nullptr);  // in-place branch cache, as in etv_commit_accepted_kv
+    if (in_place && prefix_len_out == prefix_len) return ETV_ERR_INVALID_ARG;
     if (h->B == 0) return ETV_OK;
     const int32_t B = h->B, T_max = h->T_max;
     hipStream_t s = etv::as_stream(stream);
@@ -229,8 +232,10 @@ extern "C" int32_t etv_verify_epilogue(const etv_commit_desc *h, const float *lo
     hipLaunchKernelGGL(etv::verify_epilogue_kernel, dim3((unsigned)(B + gather_blocks)), dim3(256), 0, s, *h, pval, pidx, chunks, tokens, retrieve,
                        n_nodes, (int)L_max, (int)dummy, static_cast<const uint8_t *>(src), row_bytes, safe, pvalid,
                        static_cast<uint8_t *>(gathered), argmax, len, best, accept_len, acc_nodes, bonus, block_table,
-                       prefix_len, capacity, prefix_len_out, slot_map, status);
+                       prefix_len, capacity, prefix_len_out, slot_map, status, in_place ? 1 : 0);
     rc = etv::check_launch();
     if (rc != ETV_OK) return rc;
+    if (in_place)
+        return etv::launch_commit_compact(h, k_cache, v_cache, block_table, prefix_len, acc_nodes, accept_len, slot_map, s);
     return etv::launch_commit_copy(h, kt, vt, k_cache, v_cache, acc_nodes, slot_map, s);
 }

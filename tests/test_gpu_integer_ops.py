@@ -317,3 +317,83 @@ def test_fused_epilogue_matches_gather_acceptance_and_commit():
     assert rc["status"][2] != 0 and np.all(np.delete(rc["status"], 2) == 0)
     assert len(set(rp["accept_len"].tolist())) > 1
     _epilogue_case(synth.config5(16, 4, B=6, P=200), dummy=3)               # padding-heavy path table, dummy != 0
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_in_place_branch_cache_attention_and_commit(paged):
+    """The tree K/V live in the cache itself behind the prefix (no separate tree buffer): attention must give the
+    bits it gives with the separate buffer, and the commit must compact the accepted rows as the oracle does,
+    through the plain and the fused entry points, including destinations that were sources of earlier rows."""
+    from gpu_helpers import gpu_attention
+    rng = np.random.default_rng(88)
+    B, T, L = 5, 40, 2
+    parents = [random_tree(rng, T) for _ in range(B)]
+    wl = synth.assemble("tail", rng, parents, [300, 77, 64, 1, 129], Hq=8, Hkv=2, d=128, dtype="bf16", V=512, W=T,
+                        paged=paged, T_max=T, spare_blocks=3, tail_room=T)
+    wl.n_nodes[1] = 17                                   # one padded sequence
+    kt = np.stack([wl.kt] + [synth._values(rng, wl.kt.shape, "bf16") for _ in range(L - 1)])
+    vt = np.stack([wl.vt] + [synth._values(rng, wl.vt.shape, "bf16") for _ in range(L - 1)])
+    kc = np.stack([wl.k_cache] + [synth._values(rng, wl.k_cache.shape, "bf16") for _ in range(L - 1)])
+    vc = np.stack([wl.v_cache] + [synth._values(rng, wl.v_cache.shape, "bf16") for _ in range(L - 1)])
+    for b in range(B):                                   # the verification pass has extended the cache in place
+        for j in range(int(wl.n_nodes[b])):
+            pos = int(wl.prefix_len[b]) + j
+            if paged:
+                blk, off = wl.block_table[b, pos // synth.BLOCK], pos % synth.BLOCK
+                kc[:, blk, :, off] = kt[:, b, j]; vc[:, blk, :, off] = vt[:, b, j]
+            else:
+                kc[:, b, pos] = kt[:, b, j]; vc[:, b, pos] = vt[:, b, j]
+    wl.k_cache, wl.v_cache = kc[0].copy(), vc[0].copy()
+    d = DevWorkload(wl)
+    m = api.build_tree_mask(d.parent, d.n_nodes)
+    for kw in (dict(), dict(kv_split=64), dict(flags=api.ATTN_FLAG_GENERIC)):
+        sep, lse_sep = gpu_attention(d, m["bitmask"], **kw)
+        tail, lse_tail = api.tree_verify_attention(d.q, d.k_cache, d.v_cache, d.prefix_len, None, None, m["bitmask"],
+                                                   d.n_nodes, P_max=d.P_max, block_table=d.block_table, **kw)
+        torch.cuda.synchronize()
+        assert torch.equal(sep, tail) and torch.equal(lse_sep, lse_tail), kw
+    # commit: full accepted paths of different leaves
+    acc = np.zeros((B, T), dtype=np.int32)
+    A = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        path = [int(x) for x in wl.retrieve[b, b % wl.n_paths[b]] if 0 <= x < wl.n_nodes[b]]
+        A[b] = len(path) - 1
+        acc[b, :len(path)] = path
+    okc, ovc = kc.copy(), vc.copy()
+    rc = oracle.commit_accepted_kv(None, None, okc, ovc, wl.prefix_len, wl.capacity, wl.n_nodes, acc, A,
+                                   block_table=wl.block_table, T_max=T)
+    assert np.all(rc["status"] == 0)
+    dkc, dvc = to_dev(kc), to_dev(vc)
+    c = api.commit_accepted_kv(None, None, dkc, dvc, d.prefix_len, d.capacity, d.n_nodes, to_dev(acc), to_dev(A),
+                               block_table=d.block_table, T_max=T)
+    torch.cuda.synchronize()
+    for key in rc:
+        assert np.array_equal(bits_of(c[key]), rc[key]), key
+    assert np.array_equal(bits_of(dkc), okc) and np.array_equal(bits_of(dvc), ovc)
+    # a sequence without room for its tail is refused and left alone
+    cap = wl.capacity.copy(); cap[0] = wl.prefix_len[0] + 3
+    okc2, ovc2 = kc.copy(), vc.copy()
+    rc2 = oracle.commit_accepted_kv(None, None, okc2, ovc2, wl.prefix_len, cap, wl.n_nodes, acc, A,
+                                    block_table=wl.block_table, T_max=T)
+    dkc2, dvc2 = to_dev(kc), to_dev(vc)
+    c2 = api.commit_accepted_kv(None, None, dkc2, dvc2, d.prefix_len, to_dev(cap), d.n_nodes, to_dev(acc), to_dev(A),
+                                block_table=d.block_table, T_max=T)
+    torch.cuda.synchronize()
+    assert rc2["status"][0] != 0
+    for key in rc2:
+        assert np.array_equal(bits_of(c2[key]), rc2[key]), key
+    assert np.array_equal(bits_of(dkc2), okc2) and np.array_equal(bits_of(dvc2), ovc2)
+    # the fused epilogue over the in-place branch cache: acceptance from the logits, then compaction
+    rp = oracle.evaluate_posterior(wl.logits, wl.tokens, wl.retrieve, wl.n_nodes)
+    okc3, ovc3 = kc.copy(), vc.copy()
+    rc3 = oracle.commit_accepted_kv(None, None, okc3, ovc3, wl.prefix_len, wl.capacity, wl.n_nodes, rp["acc_nodes"],
+                                    rp["accept_len"], block_table=wl.block_table, T_max=T)
+    dkc3, dvc3 = to_dev(kc), to_dev(vc)
+    g3, p3, c3 = api.verify_epilogue(d.logits, d.tokens, d.retrieve, d.n_nodes, None, None, dkc3, dvc3, d.prefix_len,
+                                     d.capacity, block_table=d.block_table)
+    torch.cuda.synchronize()
+    for key in rp:
+        assert np.array_equal(bits_of(p3[key]), rp[key]), key
+    for key in rc3:
+        assert np.array_equal(bits_of(c3[key]), rc3[key]), key
+    assert np.array_equal(bits_of(dkc3), okc3) and np.array_equal(bits_of(dvc3), ovc3)
