@@ -23,6 +23,7 @@ _lib = None
 
 TREE_RANGE, TREE_CYCLE, TREE_CLOSURE = 1, 2, 4
 COMMIT_CAPACITY, COMMIT_BAD_NODE, COMMIT_BAD_LEN, COMMIT_BAD_BLOCK = 1, 2, 4, 8
+BRANCH_NO_BLOCKS, BRANCH_BAD_FREE = 16, 32
 
 
 def build(force: bool = True) -> str:
@@ -196,3 +197,55 @@ def commit_accepted_kv(kt, vt, k_cache, v_cache, prefix_len, capacity, n_nodes, 
            _p(_i32(accept_len)), W, _p(plo), _p(slot), _p(st))
     assert rc == 0, rc
     return dict(prefix_len_out=plo, slot_map=slot, status=st)
+
+
+def replicate_branches(k_cache, v_cache, block_table, prefix_len, tail_len, N: int, free_blocks):
+    """Paged caches [Lyr, nb, Hkv, bs, d] (the partly filled blocks are copied IN PLACE into the branches' own
+    blocks); returns branch_table [B, N, max_blocks], block_base [B], n_taken, status [B]."""
+    assert k_cache.flags["C_CONTIGUOUS"] and v_cache.flags["C_CONTIGUOUS"]
+    Lyr, nb, Hkv, bs, d = k_cache.shape
+    block_table, free_blocks = _i32(block_table), _i32(free_blocks)
+    B, max_blocks = block_table.shape
+    bt = np.zeros((B, N, max_blocks), dtype=np.int32)
+    base = np.zeros(B, dtype=np.int32)
+    taken = np.zeros(1, dtype=np.int32)
+    st = np.zeros(B, dtype=np.int32)
+    f = lib().orc_replicate_branches
+    f.argtypes = ([C.c_int] * 6 + [C.c_void_p] * 2 + [C.c_size_t, C.c_void_p] + [C.c_int] * 3 + [C.c_void_p] * 3
+                  + [C.c_int] + [C.c_void_p] * 4)
+    rc = f(B, N, Hkv, d, k_cache.dtype.itemsize, Lyr, _p(k_cache), _p(v_cache), int(np.prod(k_cache.shape[1:])),
+           _p(block_table), bs, max_blocks, nb, _p(_i32(prefix_len)), _p(_i32(tail_len)), _p(free_blocks),
+           len(free_blocks), _p(bt), _p(base), _p(taken), _p(st))
+    assert rc == 0, rc
+    return dict(branch_table=bt, block_base=base, n_taken=int(taken[0]), status=st)
+
+
+def commit_path_indices(src_k, src_v, dst_k, dst_v, path_indices, src_len, new_len, *, src_table=None,
+                        dst_table=None, fast: bool = False):
+    """Caches [Lyr, ...]: contiguous [B, P_cap, Hkv, d] (source and destination are different arrays) or paged
+    [nb, Hkv, bs, d] (one pool may serve as both; dst_table is then updated IN PLACE with the shared blocks).
+    The destination cache is written IN PLACE; returns kept_len, status."""
+    for a in (src_k, src_v, dst_k, dst_v):
+        assert a.flags["C_CONTIGUOUS"]
+    assert src_k.shape == dst_k.shape
+    path_indices = _i32(path_indices)
+    B, L_cap = path_indices.shape
+    Lyr, eb = src_k.shape[0], src_k.dtype.itemsize
+    if src_table is not None:
+        src_table = _i32(src_table)
+        assert dst_table.dtype == np.int32 and dst_table.flags["C_CONTIGUOUS"] and dst_table.shape == src_table.shape
+        nb, Hkv, bs, d = src_k.shape[1:]
+        max_blocks, P_cap = src_table.shape[1], 0
+    else:
+        P_cap, Hkv, d = src_k.shape[2:]
+        nb = bs = max_blocks = 0
+    kept = np.zeros(B, dtype=np.int32)
+    st = np.zeros(B, dtype=np.int32)
+    f = lib().orc_commit_path_indices
+    f.argtypes = ([C.c_int] * 5 + [C.c_void_p] * 4 + [C.c_size_t] + [C.c_void_p] * 2 + [C.c_int] * 4 + [C.c_void_p]
+                  + [C.c_int] + [C.c_void_p] * 2 + [C.c_int] + [C.c_void_p] * 2)
+    rc = f(B, Hkv, d, eb, Lyr, _p(src_k), _p(src_v), _p(dst_k), _p(dst_v), int(np.prod(src_k.shape[1:])),
+           _p(src_table), _p(dst_table), bs, max_blocks, nb, P_cap, _p(path_indices), L_cap, _p(_i32(src_len)),
+           _p(_i32(new_len)), int(fast), _p(kept), _p(st))
+    assert rc == 0, rc
+    return dict(kept_len=kept, status=st)

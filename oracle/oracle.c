@@ -17,8 +17,10 @@
  * (one-node tree = decode attention, chain = causal attention, per-node
  * sequential equivalence), a hand-worked 7-node example, sequential-append
  * commit, and for the path table parent walks from every leaf plus the closed
- * forms of a chain, a star and a complete binary tree.  No function here is
- * "parity unpinned".
+ * forms of a chain, a star and a complete binary tree; branch replication
+ * against the deep copy it encodes (content, isolation, block accounting) and
+ * the path-index commit against numpy's gather of the logical rows and the
+ * length-based commit.  No function here is "parity unpinned".
  *
  * Conventions (shared with the seeded generators):
  *   node rows 0..n_nodes[b]-1 of sequence b are valid, row 0 is the root (the
@@ -608,6 +610,183 @@ int orc_lm_head_argmax(const void *hidden, const void *weight, int dtype, const 
         }
         argmax[r] = bi;
         if (maxval) maxval[r] = best;
+    }
+    return ORC_OK;
+}
+
+/* status bits of the branch-cache calls below (they share the commit bits above) */
+#define ORC_BRANCH_NO_BLOCKS 16 /* the free list is shorter than what the call needs      */
+#define ORC_BRANCH_BAD_FREE 32  /* a free-list entry this sequence would use is no block   */
+
+/* byte offset of (position j, KV head hh) inside one layer of a cache */
+static size_t cache_row_off(const int32_t *table_row, int block_size, int Hkv, int P_cap, int b, size_t j, int hh,
+                            size_t rowb) {
+    if (table_row) {
+        int blk = table_row[j / block_size];
+        return (((size_t)blk * Hkv + hh) * block_size + j % block_size) * rowb;
+    }
+    return (((size_t)b * P_cap + j) * Hkv + hh) * rowb;
+}
+
+/* ------------------------------------------------------------------------
+ * Branch replication on a paged cache.  Section 3.1: every speculative
+ * iteration creates N branch caches B_i <- Replicate(C*), each an isolated
+ * replica of the committed cache that the teacher pass then extends in place;
+ * isolation means extending one branch mutates neither C* nor another branch.
+ * The paper replicates by deep copy.  Here the replica is an encoding: a block
+ * table per branch that SHARES the blocks lying wholly inside the committed
+ * prefix (nothing writes below prefix_len) and owns private blocks from the
+ * position prefix_len on - the partly filled block that holds position
+ * prefix_len (its committed rows copied in) and the blocks the tail will use.
+ * The pins compare the logical content against the deep copy.
+ *
+ * Rule (what the GPU side must reproduce exactly):
+ *   first_b = P_b / bs; last_b = ceil((P_b + tail_b) / bs); need_b = last_b - first_b
+ *   (0 for a sequence with an error); block_base[b] = N * sum_{b' < b} need_b';
+ *   branch i of sequence b owns free_blocks[block_base[b] + i*need_b + k] as its
+ *   logical block first_b + k.  n_taken = N * sum_b need_b.  If that exceeds n_free,
+ *   nothing is written to the cache, n_taken = 0 and every sequence that needs
+ *   blocks reports NO_BLOCKS.  Table rows of a failed sequence are all -1; entries
+ *   from last_b on are -1.
+ *   block_table [B, max_blocks]; branch_table [B, N, max_blocks]; status [B]
+ * ---------------------------------------------------------------------- */
+int orc_replicate_branches(int B, int N, int Hkv, int d, int elem_bytes, int n_layers, void *k_cache, void *v_cache,
+                           size_t cache_layer_stride, const int32_t *block_table, int block_size, int max_blocks,
+                           int num_blocks, const int32_t *prefix_len, const int32_t *tail_len,
+                           const int32_t *free_blocks, int n_free, int32_t *branch_table, int32_t *block_base,
+                           int32_t *n_taken, int32_t *status) {
+    if (B < 0 || N < 1 || block_size < 1 || max_blocks < 1 || !block_table) return ORC_ERR_ARG;
+    size_t rowb = (size_t)d * elem_bytes;
+    int *need = (int *)calloc((size_t)B + 1, sizeof(int));
+    if (!need) return ORC_ERR_NOMEM;
+    long total = 0;
+    for (int b = 0; b < B; b++) {
+        long P = prefix_len[b], t = tail_len[b];
+        int32_t st = 0;
+        if (P < 0 || t < 0) st |= ORC_COMMIT_BAD_LEN;
+        if (!st) {
+            long last = (P + t + block_size - 1) / block_size;
+            if (last > max_blocks) st |= ORC_COMMIT_CAPACITY;
+            if (!st)
+                for (long k = 0; k < (P + block_size - 1) / block_size; k++) {
+                    int blk = block_table[(size_t)b * max_blocks + k];
+                    if (blk < 0 || blk >= num_blocks) st |= ORC_COMMIT_BAD_BLOCK;
+                }
+            if (!st) need[b] = (int)(last - P / block_size);
+        }
+        status[b] = st;
+        block_base[b] = (int32_t)total;
+        total += (long)N * need[b];
+    }
+    int fits = total <= n_free;
+    *n_taken = fits ? (int32_t)total : 0;
+    for (int b = 0; b < B; b++) {
+        if (!fits && need[b]) status[b] |= ORC_BRANCH_NO_BLOCKS;
+        if (fits && !status[b])
+            for (int x = 0; x < N * need[b]; x++) {
+                int blk = free_blocks[block_base[b] + x];
+                if (blk < 0 || blk >= num_blocks) status[b] |= ORC_BRANCH_BAD_FREE;
+            }
+        int P = prefix_len[b], first = status[b] ? 0 : P / block_size;
+        for (int i = 0; i < N; i++) {
+            int32_t *row = branch_table + ((size_t)b * N + i) * max_blocks;
+            for (int k = 0; k < max_blocks; k++) {
+                if (status[b] || k >= first + need[b]) row[k] = -1;
+                else if (k < first) row[k] = block_table[(size_t)b * max_blocks + k];
+                else row[k] = free_blocks[block_base[b] + i * need[b] + (k - first)];
+            }
+            if (status[b] || P % block_size == 0) continue;
+            /* the committed rows of the partly filled block move into the branch's own copy of it */
+            for (int l = 0; l < n_layers; l++)
+                for (int kv = 0; kv < 2; kv++)
+                    for (int hh = 0; hh < Hkv; hh++) {
+                        char *cache = (char *)(kv ? v_cache : k_cache) + (size_t)l * cache_layer_stride * elem_bytes;
+                        for (int j = first * block_size; j < P; j++)
+                            memcpy(cache + cache_row_off(row, block_size, Hkv, 0, b, (size_t)j, hh, rowb),
+                                   cache + cache_row_off(block_table + (size_t)b * max_blocks, block_size, Hkv, 0, b,
+                                                         (size_t)j, hh, rowb),
+                                   rowb);
+                    }
+        }
+    }
+    free(need);
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------
+ * Commit by path indices.  Section 3.1 "Commit by path indices and
+ * prefix-sharing fast reorder": path_indices maps the next step's prefix
+ * sequence to positions of the selected branch cache; the committed cache is
+ * the branch cache gathered along the sequence axis,
+ *     new[j] = branch[path_indices[j]],  0 <= j < new_len,
+ * for every layer, KV head, K and V ("full reordering", any index order,
+ * repeats allowed).  The fast path keeps the part of the prefix whose order
+ * the indices preserve and gathers only the rest; it is decided from the
+ * indices themselves, so any inconsistency simply shortens what is kept, down
+ * to the full reorder.
+ *
+ * The source (branch) and destination (committed) caches are separate storage:
+ * contiguous [B, P_cap, Hkv, d] buffers, or two block tables over one pool.
+ * Paged with fast != 0: keep_b = the longest j <= new_len with path_indices[k] = k
+ * for all k < j, rounded down to whole blocks; the destination table takes the
+ * source's block ids for those blocks (sharing them) and rows >= keep_b are
+ * gathered into the destination's own blocks.  Otherwise keep_b = 0.  The source
+ * is read completely before anything is written.  A sequence with an error
+ * writes nothing and leaves its destination table row alone.
+ *   path_indices [B, L_cap]; src_len, new_len, kept_len, status [B]
+ * ---------------------------------------------------------------------- */
+int orc_commit_path_indices(int B, int Hkv, int d, int elem_bytes, int n_layers, const void *src_k, const void *src_v,
+                            void *dst_k, void *dst_v, size_t cache_layer_stride, const int32_t *src_table,
+                            int32_t *dst_table, int block_size, int max_blocks, int num_blocks, int P_cap,
+                            const int32_t *path_indices, int L_cap, const int32_t *src_len, const int32_t *new_len,
+                            int fast, int32_t *kept_len, int32_t *status) {
+    if (B < 0 || L_cap < 1 || (src_table != NULL) != (dst_table != NULL)) return ORC_ERR_ARG;
+    if (src_table && (block_size < 1 || max_blocks < 1)) return ORC_ERR_ARG;
+    size_t rowb = (size_t)d * elem_bytes;
+    for (int b = 0; b < B; b++) {
+        long Ls = src_len[b], Ln = new_len[b];
+        long cap = src_table ? (long)max_blocks * block_size : P_cap;
+        const int32_t *idx = path_indices + (size_t)b * L_cap;
+        const int32_t *srow = src_table ? src_table + (size_t)b * max_blocks : NULL;
+        int32_t *drow = dst_table ? dst_table + (size_t)b * max_blocks : NULL;
+        int32_t st = 0;
+        kept_len[b] = 0;
+        if (Ln < 0 || Ln > L_cap || Ls < 0 || Ls > cap) st |= ORC_COMMIT_BAD_LEN;
+        if (!st && Ln > cap) st |= ORC_COMMIT_CAPACITY;
+        long keep = 0;
+        if (!st) {
+            for (long j = 0; j < Ln; j++)
+                if (idx[j] < 0 || idx[j] >= Ls) st |= ORC_COMMIT_BAD_NODE;
+            if (fast && src_table) {
+                while (keep < Ln && idx[keep] == keep) keep++;
+                keep = keep / block_size * block_size;
+            }
+            if (src_table) {
+                for (long k = 0; k < (Ls + block_size - 1) / block_size; k++)
+                    if (srow[k] < 0 || srow[k] >= num_blocks) st |= ORC_COMMIT_BAD_BLOCK;
+                for (long k = keep / block_size; k < (Ln + block_size - 1) / block_size; k++)
+                    if (drow[k] < 0 || drow[k] >= num_blocks) st |= ORC_COMMIT_BAD_BLOCK;
+            }
+        }
+        status[b] = st;
+        if (st) continue;
+        kept_len[b] = (int32_t)keep;
+        char *snap = (char *)malloc((size_t)(Ls ? Ls : 1) * rowb);
+        if (!snap) return ORC_ERR_NOMEM;
+        for (int l = 0; l < n_layers; l++)
+            for (int kv = 0; kv < 2; kv++)
+                for (int hh = 0; hh < Hkv; hh++) {
+                    const char *src = (const char *)(kv ? src_v : src_k) + (size_t)l * cache_layer_stride * elem_bytes;
+                    char *dst = (char *)(kv ? dst_v : dst_k) + (size_t)l * cache_layer_stride * elem_bytes;
+                    for (long j = 0; j < Ls; j++)
+                        memcpy(snap + (size_t)j * rowb,
+                               src + cache_row_off(srow, block_size, Hkv, P_cap, b, (size_t)j, hh, rowb), rowb);
+                    for (long j = keep; j < Ln; j++)
+                        memcpy(dst + cache_row_off(drow, block_size, Hkv, P_cap, b, (size_t)j, hh, rowb),
+                               snap + (size_t)idx[j] * rowb, rowb);
+                }
+        free(snap);
+        for (long k = 0; src_table && k < keep / block_size; k++) drow[k] = srow[k];
     }
     return ORC_OK;
 }
