@@ -62,6 +62,9 @@ extern "C" {
 #define ETV_COMMIT_BAD_NODE 2  /* an accepted node index is not a valid node row                       */
 #define ETV_COMMIT_BAD_LEN 4   /* accept_len outside [0, W-1]                                          */
 #define ETV_COMMIT_BAD_BLOCK 8 /* a needed block-table entry is outside [0, num_blocks)                */
+/* additional status bits of etv_replicate_branches */
+#define ETV_BRANCH_NO_BLOCKS 16 /* the free list is shorter than what the call needs: nothing was taken   */
+#define ETV_BRANCH_BAD_FREE 32  /* a free-list entry this sequence would use is outside [0, num_blocks)   */
 
 #define ETV_MAX_TREE 256       /* largest T_max of the mask builder, gather and posterior              */
 #define ETV_ATTN_MAX_TREE 256  /* largest T_max of tree_verify_attention                               */
@@ -321,6 +324,80 @@ ETV_API int32_t etv_verify_epilogue(const etv_commit_desc *h_desc, const float *
                             const int32_t *prefix_len, const int32_t *capacity, const int32_t *n_nodes,
                             int32_t *prefix_len_out, int32_t *slot_map, int32_t *status, void *workspace,
                             size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * Branch caches over a paged cache pool -- Section 3.1 "Branchable KV-cache
+ * abstraction".  The two calls below work on block tables over ONE pool
+ * (k_cache / v_cache, per-layer layout [num_blocks, Hkv, block_size, d] as in
+ * attention; layer l starts cache_layer_stride elements after layer l-1).
+ * ------------------------------------------------------------------------- */
+typedef struct etv_cache_desc {
+    int32_t B, Hkv, d;
+    int32_t elem_bytes; /* 2 (bf16) or 4 (fp32) */
+    int32_t n_layers;
+    int32_t block_size; /* > 0: paged; 0: contiguous (etv_commit_path_indices only) */
+    int32_t max_blocks; /* row length of every block table */
+    int32_t num_blocks;
+    int32_t P_cap;      /* contiguous: rows per sequence */
+    int32_t reserved;
+    int64_t cache_layer_stride;
+} etv_cache_desc;
+
+/* replicate_branches -- B_i <- Replicate(C*) for N branches per sequence (Section 3.1), as copy-on-write block
+ * tables instead of a deep copy: a branch shares every block that lies wholly inside the committed prefix (nothing
+ * writes below prefix_len) and owns the blocks from position prefix_len[b] on -- the partly filled block that
+ * holds position prefix_len[b], with its committed rows copied in, and the blocks its tail of tail_len[b] rows
+ * will reach.  Extending a branch in place therefore touches neither the committed cache nor another branch, and
+ * every branch reads the committed rows.  Branch tables are ordinary block tables: attention, commit and the
+ * epilogue take branch_table viewed as [B*N, max_blocks] with the per-sequence arrays repeated N times.
+ *
+ *   first = prefix_len[b] / block_size, last = ceil((prefix_len[b] + tail_len[b]) / block_size),
+ *   need_b = last - first (0 for a sequence with an error), block_base[b] = N * sum of need over b' < b;
+ *   branch i owns free_blocks[block_base[b] + i*need_b + k] as logical block first + k.
+ *   n_taken[0] = N * sum_b need_b: the caller's free list continues behind it.  If n_taken would exceed n_free,
+ *   nothing is copied, n_taken[0] = 0 and every sequence that needs blocks gets ETV_BRANCH_NO_BLOCKS.
+ *   Status bits per sequence: ETV_COMMIT_BAD_LEN (negative length), ETV_COMMIT_CAPACITY (last > max_blocks),
+ *   ETV_COMMIT_BAD_BLOCK (a committed block outside the pool), ETV_BRANCH_NO_BLOCKS, ETV_BRANCH_BAD_FREE.
+ *   The table rows of a failed sequence are -1 throughout; entries from `last` on are -1.
+ *
+ *  block_table  in  int32 [B, max_blocks]     the committed cache's table
+ *  prefix_len, tail_len in int32 [B]
+ *  free_blocks  in  int32 [n_free]            distinct blocks that no table uses (the caller's allocator)
+ *  branch_table out int32 [B, N, max_blocks]
+ *  block_base   out int32 [B];  n_taken out int32 [1];  status out int32 [B]
+ * All device pointers.  Requires block_size > 0 and d * elem_bytes % 16 == 0. */
+ETV_API int32_t etv_replicate_branches(const etv_cache_desc *h_desc, void *k_cache, void *v_cache,
+                               const int32_t *block_table, const int32_t *prefix_len, const int32_t *tail_len,
+                               int32_t N, const int32_t *free_blocks, int32_t n_free, int32_t *branch_table,
+                               int32_t *block_base, int32_t *n_taken, int32_t *status, void *stream);
+
+/* commit_path_indices -- Section 3.1 "Commit by path indices and prefix-sharing fast reorder": path_indices maps
+ * the next step's prefix sequence to positions of the selected branch cache, and the committed cache is the branch
+ * cache gathered along the sequence axis,
+ *     new[b, j] = branch[b, path_indices[b, j]],   0 <= j < new_len[b],
+ * for every layer, KV head, K and V (any order, repeats allowed: the general full reorder).  Source and
+ * destination are separate storage: two contiguous buffers [B, P_cap, Hkv, d] (src != dst), or two block tables
+ * over one pool whose written blocks are not blocks of the source (the caller's contract).
+ * fast != 0 (paged only): the part of the prefix whose order the indices preserve is not moved --
+ * kept_len[b] = the longest j <= new_len[b] with path_indices[b, k] = k for all k < j, rounded down to whole blocks;
+ * dst_table takes the source's block ids for those blocks and only rows >= kept_len[b] are gathered into the
+ * destination's own blocks.  The decision comes from the indices themselves, so an inconsistent prefix shortens
+ * what is kept, down to the full reorder (kept_len = 0, also for fast = 0 and for contiguous caches; the
+ * prefix-sharing commit of a contiguous cache is etv_commit_accepted_kv).
+ *   Status bits: ETV_COMMIT_BAD_LEN (new_len outside [0, L_cap] or src_len outside the source's capacity),
+ *   ETV_COMMIT_CAPACITY (new_len beyond the destination), ETV_COMMIT_BAD_NODE (an index outside [0, src_len)),
+ *   ETV_COMMIT_BAD_BLOCK (a needed table entry outside the pool).  A failed sequence writes nothing and keeps
+ *   its dst_table row.
+ *
+ *  src_k, src_v in; dst_k, dst_v out   (paged: may be the same pool)
+ *  src_table in int32 [B, max_blocks]; dst_table in/out int32 [B, max_blocks] (NULL when contiguous)
+ *  path_indices in int32 [B, L_cap]; src_len, new_len in int32 [B]; kept_len, status out int32 [B]
+ * All device pointers.  Requires d * elem_bytes % 16 == 0. */
+ETV_API int32_t etv_commit_path_indices(const etv_cache_desc *h_desc, const void *src_k, const void *src_v, void *dst_k,
+                                void *dst_v, const int32_t *src_table, int32_t *dst_table,
+                                const int32_t *path_indices, int32_t L_cap, const int32_t *src_len,
+                                const int32_t *new_len, int32_t fast, int32_t *kept_len, int32_t *status,
+                                void *stream);
 
 #ifdef __cplusplus
 }

@@ -22,6 +22,7 @@ _lib = None
 F32, BF16 = 0, 1
 TREE_RANGE, TREE_CYCLE, TREE_CLOSURE = 1, 2, 4
 COMMIT_CAPACITY, COMMIT_BAD_NODE, COMMIT_BAD_LEN, COMMIT_BAD_BLOCK = 1, 2, 4, 8
+BRANCH_NO_BLOCKS, BRANCH_BAD_FREE = 16, 32
 ATTN_FLAG_GENERIC = 1
 ATTN_FLAG_SMALL_WG = 2
 ATTN_FLAG_WHOLE_TILE = 4
@@ -33,7 +34,7 @@ EXPORTS = ("etv_status_string", "etv_version", "etv_last_hip_error", "etv_hbm_re
            "etv_tree_verify_attention_workspace_bytes", "etv_tree_verify_attention", "etv_safe_gather_paths",
            "etv_evaluate_posterior_workspace_bytes", "etv_evaluate_posterior", "etv_commit_accepted_kv",
            "etv_verify_epilogue", "etv_lm_head_argmax_workspace_bytes", "etv_lm_head_argmax",
-           "etv_lm_head_packed_bytes", "etv_pack_lm_head")
+           "etv_lm_head_packed_bytes", "etv_pack_lm_head", "etv_replicate_branches", "etv_commit_path_indices")
 
 
 class AttnDesc(C.Structure):
@@ -46,6 +47,11 @@ class CommitDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "T_max", "Hkv", "d", "elem_bytes", "n_layers", "W", "block_size",
                                          "max_blocks", "num_blocks", "P_cap", "reserved")] + \
                [("cache_layer_stride", C.c_int64)]
+
+
+class CacheDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "Hkv", "d", "elem_bytes", "n_layers", "block_size", "max_blocks",
+                                         "num_blocks", "P_cap", "reserved")] + [("cache_layer_stride", C.c_int64)]
 
 
 class EtvError(RuntimeError):
@@ -96,6 +102,10 @@ def lib():
         l.etv_evaluate_posterior.argtypes = [vp] * 4 + [i32] * 6 + [vp] * 7 + [sz, vp]
         l.etv_commit_accepted_kv.restype = i32
         l.etv_commit_accepted_kv.argtypes = [C.POINTER(CommitDesc)] + [vp] * 14
+        l.etv_replicate_branches.restype = i32
+        l.etv_replicate_branches.argtypes = [C.POINTER(CacheDesc)] + [vp] * 5 + [i32, vp, i32] + [vp] * 5
+        l.etv_commit_path_indices.restype = i32
+        l.etv_commit_path_indices.argtypes = [C.POINTER(CacheDesc)] + [vp] * 7 + [i32, vp, vp, i32, vp, vp, vp]
         _lib = l
     return _lib
 
@@ -393,3 +403,47 @@ def commit_accepted_kv(kt, vt, k_cache, v_cache, prefix_len, capacity, n_nodes, 
                                       _ptr(status), _stream())
     _check("etv_commit_accepted_kv", rc)
     return dict(prefix_len_out=prefix_len_out, slot_map=slot, status=status)
+
+
+def _cache_desc(cache: torch.Tensor, B: int, table: Optional[torch.Tensor]) -> CacheDesc:
+    Lyr = cache.shape[0]
+    dsc = CacheDesc(B=B, Hkv=0, d=cache.shape[4], elem_bytes=cache.element_size(), n_layers=Lyr, block_size=0,
+                    max_blocks=0, num_blocks=0, P_cap=0, reserved=0,
+                    cache_layer_stride=cache.stride(0) if Lyr > 1 else cache[0].numel())
+    if table is not None:
+        dsc.Hkv, dsc.block_size, dsc.max_blocks, dsc.num_blocks = cache.shape[2], cache.shape[3], table.shape[-1], cache.shape[1]
+    else:
+        dsc.Hkv, dsc.P_cap = cache.shape[3], cache.shape[2]
+    return dsc
+
+
+def replicate_branches(k_cache, v_cache, block_table, prefix_len, tail_len, N: int, free_blocks):
+    """Paged caches [Lyr, nb, Hkv, bs, d]; block_table [B, max_blocks]; free_blocks int32 [n_free].
+    Returns branch_table [B, N, max_blocks], block_base [B], n_taken [1], status [B] (device tensors)."""
+    B, dev = block_table.shape[0], k_cache.device
+    dsc = _cache_desc(k_cache, B, block_table)
+    bt = torch.empty((B, N, block_table.shape[1]), dtype=torch.int32, device=dev)
+    base = torch.empty((B,), dtype=torch.int32, device=dev)
+    taken = torch.empty((1,), dtype=torch.int32, device=dev)
+    status = torch.empty((B,), dtype=torch.int32, device=dev)
+    rc = lib().etv_replicate_branches(C.byref(dsc), _ptr(k_cache), _ptr(v_cache), _ptr(block_table), _ptr(prefix_len),
+                                      _ptr(tail_len), N, _ptr(free_blocks), free_blocks.numel(), _ptr(bt), _ptr(base),
+                                      _ptr(taken), _ptr(status), _stream())
+    _check("etv_replicate_branches", rc)
+    return dict(branch_table=bt, block_base=base, n_taken=taken, status=status)
+
+
+def commit_path_indices(src_k, src_v, dst_k, dst_v, path_indices, src_len, new_len, *, src_table=None, dst_table=None,
+                        fast: bool = False):
+    """Caches [Lyr, B, P_cap, Hkv, d] (two buffers) or [Lyr, nb, Hkv, bs, d] with two block tables (dst_table is
+    updated in place with the shared blocks).  Returns kept_len, status."""
+    B, L_cap = path_indices.shape
+    dev = src_k.device
+    dsc = _cache_desc(src_k, B, src_table)
+    kept = torch.empty((B,), dtype=torch.int32, device=dev)
+    status = torch.empty((B,), dtype=torch.int32, device=dev)
+    rc = lib().etv_commit_path_indices(C.byref(dsc), _ptr(src_k), _ptr(src_v), _ptr(dst_k), _ptr(dst_v), _ptr(src_table),
+                                       _ptr(dst_table), _ptr(path_indices), L_cap, _ptr(src_len), _ptr(new_len),
+                                       int(fast), _ptr(kept), _ptr(status), _stream())
+    _check("etv_commit_path_indices", rc)
+    return dict(kept_len=kept, status=status)

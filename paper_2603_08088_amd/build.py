@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libeagletv.so")
-SOURCES = ["api.hip", "mask.hip", "attention.hip", "posterior.hip", "commit.hip", "lmhead.hip"]
+SOURCES = ["api.hip", "mask.hip", "attention.hip", "posterior.hip", "commit.hip", "lmhead.hip", "branch.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

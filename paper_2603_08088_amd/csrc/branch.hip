@@ -1,0 +1,332 @@
+// Branch caches over a paged pool (Section 3.1, "Branchable KV-cache abstraction"): copy-on-write replication of
+// the committed cache into N branch tables, and the commit by path indices (the general gather along the sequence
+// axis, with the prefix-sharing fast path decided from the indices).  Integer and byte work only.
+#include "etv_common.h"
+
+namespace etv {
+
+// --------------------------------------------------------------------------------------------------------------
+// replicate_branches
+// --------------------------------------------------------------------------------------------------------------
+struct ReplNeed {
+    int first, need;
+};
+__device__ __forceinline__ ReplNeed repl_need(int P, int t, int bs, int32_t st) {
+    ReplNeed r;
+    r.first = st ? 0 : P / bs;
+    r.need = st ? 0 : (int)(((long)P + t + bs - 1) / bs) - r.first;
+    return r;
+}
+
+// grid B, 256 threads: the checks of one sequence; its committed block ids are validated by all threads.
+// block_base[b] receives need_b for the scan that follows.
+__global__ void __launch_bounds__(256) replicate_check_kernel(etv_cache_desc dsc, const int32_t *__restrict__ block_table,
+                                                              const int32_t *__restrict__ prefix_len,
+                                                              const int32_t *__restrict__ tail_len,
+                                                              int32_t *__restrict__ block_base,
+                                                              int32_t *__restrict__ status) {
+    const int b = blockIdx.x;
+    const long P = prefix_len[b], t = tail_len[b];
+    const int bs = dsc.block_size;
+    int32_t st = 0;
+    if (P < 0 || t < 0) st |= ETV_COMMIT_BAD_LEN;
+    if (!st && (P + t + bs - 1) / bs > dsc.max_blocks) st |= ETV_COMMIT_CAPACITY;
+    int bad = 0;
+    if (!st) {
+        const int used = (int)((P + bs - 1) / bs);
+        for (int k = threadIdx.x; k < used; k += 256) {
+            const int blk = block_table[(size_t)b * dsc.max_blocks + k];
+            bad |= (blk < 0 || blk >= dsc.num_blocks);
+        }
+    }
+    if (__syncthreads_or(bad)) st |= ETV_COMMIT_BAD_BLOCK;
+    if (threadIdx.x == 0) {
+        status[b] = st;
+        block_base[b] = repl_need((int)P, (int)t, bs, st).need;
+    }
+}
+
+// one workgroup of 256 threads: block_base[b] = N * (sum of need over the sequences before b), the total, and the
+// all-or-nothing decision against the length of the free list.
+__global__ void __launch_bounds__(256) replicate_scan_kernel(int B, int N, int n_free, int32_t *__restrict__ block_base,
+                                                             int32_t *__restrict__ n_taken, int32_t *__restrict__ status) {
+    __shared__ int s_part[256];
+    __shared__ int s_carry;
+    const int t = threadIdx.x;
+    if (t == 0) s_carry = 0;
+    __syncthreads();
+    for (int b0 = 0; b0 < B; b0 += 256) {
+        const int b = b0 + t;
+        const int mine = b < B ? block_base[b] : 0;
+        s_part[t] = mine;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {   // inclusive scan of the 256 entries
+            const int add = t >= off ? s_part[t - off] : 0;
+            __syncthreads();
+            s_part[t] += add;
+            __syncthreads();
+        }
+        const int carry = s_carry;
+        if (b < B) block_base[b] = N * (carry + s_part[t] - mine);
+        __syncthreads();
+        if (t == 255) s_carry = carry + s_part[255];
+        __syncthreads();
+    }
+    const long total = (long)N * s_carry;
+    const bool fits = total <= n_free;
+    if (t == 0) n_taken[0] = fits ? (int32_t)total : 0;
+    if (!fits)
+        for (int b = t; b < B; b += 256) {
+            // a sequence with need > 0 is one whose successor's base moved on; the last one compares with the total
+            const long next = b + 1 < B ? block_base[b + 1] : total;
+            if (next > block_base[b]) status[b] |= ETV_BRANCH_NO_BLOCKS;
+        }
+}
+
+// grid (N, B, n_layers), 256 threads: branch i of sequence b.  Layer 0's workgroup writes the table row; every
+// layer's workgroup copies the committed rows of the partly filled block into the branch's own block.
+__global__ void __launch_bounds__(256) replicate_fill_kernel(etv_cache_desc dsc, uint8_t *__restrict__ k_cache,
+                                                             uint8_t *__restrict__ v_cache,
+                                                             const int32_t *__restrict__ block_table,
+                                                             const int32_t *__restrict__ prefix_len,
+                                                             const int32_t *__restrict__ tail_len, int N,
+                                                             const int32_t *__restrict__ free_blocks,
+                                                             const int32_t *__restrict__ block_base,
+                                                             int32_t *__restrict__ branch_table,
+                                                             int32_t *__restrict__ status) {
+    const int i = blockIdx.x, b = blockIdx.y, l = blockIdx.z, t = threadIdx.x;
+    const int bs = dsc.block_size;
+    const int32_t st = status[b] & ~ETV_BRANCH_BAD_FREE;   // that bit is this kernel's own, set below
+    const int P = prefix_len[b];
+    const ReplNeed rn = repl_need(P, tail_len[b], bs, st);
+    const int base = block_base[b];
+    int bad = 0;
+    for (int x = t; x < N * rn.need; x += 256) {
+        const int blk = free_blocks[base + x];
+        bad |= (blk < 0 || blk >= dsc.num_blocks);
+    }
+    const bool bad_free = __syncthreads_or(bad) != 0;
+    const bool failed = st != 0 || bad_free;
+    const int32_t *mine = free_blocks + base + (size_t)i * rn.need;
+    if (l == 0) {
+        if (i == 0 && t == 0 && bad_free) status[b] = st | ETV_BRANCH_BAD_FREE;
+        int32_t *row = branch_table + ((size_t)b * N + i) * dsc.max_blocks;
+        for (int k = t; k < dsc.max_blocks; k += 256) {
+            int32_t v = -1;
+            if (!failed && k < rn.first + rn.need) v = k < rn.first ? block_table[(size_t)b * dsc.max_blocks + k] : mine[k - rn.first];
+            row[k] = v;
+        }
+    }
+    const int rows = P - rn.first * bs;   // committed rows inside the partly filled block
+    if (failed || rows <= 0) return;
+    const int src_blk = block_table[(size_t)b * dsc.max_blocks + rn.first], dst_blk = mine[0];
+    const size_t head_bytes = (size_t)dsc.d * dsc.elem_bytes;
+    const int upr = (int)(head_bytes / 16);              // 16-byte units per row of one head
+    const int per_head = rows * upr;                     // the rows of a head are consecutive memory
+    const size_t layer_off = (size_t)l * (size_t)dsc.cache_layer_stride * dsc.elem_bytes;
+    for (int u = t; u < 2 * dsc.Hkv * per_head; u += 256) {
+        const int kvh = u / per_head, w = u - kvh * per_head;
+        const bool is_v = kvh >= dsc.Hkv;
+        const int hh = is_v ? kvh - dsc.Hkv : kvh;
+        uint8_t *cache = (is_v ? v_cache : k_cache) + layer_off;
+        const size_t so = ((size_t)src_blk * dsc.Hkv + hh) * bs * head_bytes + (size_t)w * 16;
+        const size_t dof = ((size_t)dst_blk * dsc.Hkv + hh) * bs * head_bytes + (size_t)w * 16;
+        *reinterpret_cast<uint4 *>(cache + dof) = *reinterpret_cast<const uint4 *>(cache + so);
+    }
+}
+
+// --------------------------------------------------------------------------------------------------------------
+// commit_path_indices
+// --------------------------------------------------------------------------------------------------------------
+// grid B, 256 threads: checks, the length of the preserved prefix, and the shared blocks of the destination table.
+__global__ void __launch_bounds__(256) path_commit_plan_kernel(etv_cache_desc dsc, const int32_t *__restrict__ src_table,
+                                                               int32_t *__restrict__ dst_table,
+                                                               const int32_t *__restrict__ path_indices, int L_cap,
+                                                               const int32_t *__restrict__ src_len,
+                                                               const int32_t *__restrict__ new_len, int fast,
+                                                               int32_t *__restrict__ kept_len,
+                                                               int32_t *__restrict__ status) {
+    __shared__ int s_min[4];
+    const int b = blockIdx.x, t = threadIdx.x;
+    const int bs = dsc.block_size;
+    const bool paged = bs > 0;
+    const long Ls = src_len[b], Ln = new_len[b];
+    const long cap = paged ? (long)dsc.max_blocks * bs : dsc.P_cap;
+    const int32_t *idx = path_indices + (size_t)b * L_cap;
+    int32_t st = 0;
+    if (Ln < 0 || Ln > L_cap || Ls < 0 || Ls > cap) st |= ETV_COMMIT_BAD_LEN;
+    if (!st && Ln > cap) st |= ETV_COMMIT_CAPACITY;
+    int bad = 0, brk = st ? 0 : (int)Ln;   // first position whose index is not the position itself
+    if (!st)
+        for (int j = t; j < (int)Ln; j += 256) {
+            const int v = idx[j];
+            bad |= (v < 0 || v >= Ls);
+            if (v != j && j < brk) brk = j;
+        }
+    if (__syncthreads_or(bad)) st |= ETV_COMMIT_BAD_NODE;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) brk = min(brk, __shfl_xor(brk, off));
+    if ((t & 63) == 0) s_min[t >> 6] = brk;
+    __syncthreads();
+    brk = min(min(s_min[0], s_min[1]), min(s_min[2], s_min[3]));
+    const int keep = (fast && paged && !(st & (ETV_COMMIT_BAD_LEN | ETV_COMMIT_CAPACITY))) ? brk / bs * bs : 0;
+    bad = 0;
+    if (paged && !(st & (ETV_COMMIT_BAD_LEN | ETV_COMMIT_CAPACITY))) {
+        for (int k = t; k < (int)((Ls + bs - 1) / bs); k += 256) {
+            const int blk = src_table[(size_t)b * dsc.max_blocks + k];
+            bad |= (blk < 0 || blk >= dsc.num_blocks);
+        }
+        for (int k = keep / bs + t; k < (int)((Ln + bs - 1) / bs); k += 256) {
+            const int blk = dst_table[(size_t)b * dsc.max_blocks + k];
+            bad |= (blk < 0 || blk >= dsc.num_blocks);
+        }
+    }
+    if (__syncthreads_or(bad)) st |= ETV_COMMIT_BAD_BLOCK;
+    if (t == 0) {
+        status[b] = st;
+        kept_len[b] = st ? 0 : keep;
+    }
+    if (!st && paged)
+        for (int k = t; k < keep / bs; k += 256) dst_table[(size_t)b * dsc.max_blocks + k] = src_table[(size_t)b * dsc.max_blocks + k];
+}
+
+// grid (row chunks, B, n_layers), 256 threads.  A chunk is one destination block (paged) or 16 rows (contiguous);
+// its rows j in [kept_len, new_len) are copied from source row path_indices[j], K and V, all heads.  Units of 16
+// bytes are numbered so that consecutive lanes write consecutive memory: (K|V, head, row, part) in a block,
+// (K|V, row, head, part) in a contiguous cache.  Eight loads are issued before their stores.
+__global__ void __launch_bounds__(256) path_commit_gather_kernel(etv_cache_desc dsc, const uint8_t *src_k,
+                                                                 const uint8_t *src_v,
+                                                                 uint8_t *dst_k, uint8_t *dst_v,
+                                                                 const int32_t *__restrict__ src_table,
+                                                                 const int32_t *__restrict__ dst_table,
+                                                                 const int32_t *__restrict__ path_indices, int L_cap,
+                                                                 const int32_t *__restrict__ new_len,
+                                                                 const int32_t *__restrict__ kept_len,
+                                                                 const int32_t *__restrict__ status) {
+    const int b = blockIdx.y, l = blockIdx.z, t = threadIdx.x;
+    if (status[b]) return;
+    const int bs = dsc.block_size;
+    const bool paged = bs > 0;
+    const int R = paged ? bs : 16;
+    const int j0 = blockIdx.x * R;
+    const int lo = max(j0, kept_len[b]), hi = min(j0 + R, new_len[b]);
+    if (lo >= hi) return;
+    const size_t head_bytes = (size_t)dsc.d * dsc.elem_bytes;
+    const int upr = (int)(head_bytes / 16);
+    const int Hkv = dsc.Hkv;
+    const size_t layer_off = (size_t)l * (size_t)dsc.cache_layer_stride * dsc.elem_bytes;
+    const int32_t *idx = path_indices + (size_t)b * L_cap;
+    const int32_t *srow = paged ? src_table + (size_t)b * dsc.max_blocks : nullptr;
+    const int dst_blk = paged ? dst_table[(size_t)b * dsc.max_blocks + blockIdx.x] : 0;
+    const int nrow = hi - lo;
+    const int total = 2 * Hkv * nrow * upr;
+    auto locate = [&](int u, const uint8_t *&from, uint8_t *&to) {
+        const int part = u % upr;
+        int q = u / upr, r, hh, kv;
+        if (paged) { r = q % nrow; q /= nrow; hh = q % Hkv; kv = q / Hkv; }
+        else       { hh = q % Hkv; q /= Hkv; r = q % nrow; kv = q / nrow; }
+        const int j = lo + r, sj = idx[j];
+        size_t so, dof;
+        if (paged) {
+            so = (((size_t)srow[sj / bs] * Hkv + hh) * bs + sj % bs) * head_bytes;
+            dof = (((size_t)dst_blk * Hkv + hh) * bs + (j - j0)) * head_bytes;
+        } else {
+            so = (((size_t)b * dsc.P_cap + sj) * Hkv + hh) * head_bytes;
+            dof = (((size_t)b * dsc.P_cap + j) * Hkv + hh) * head_bytes;
+        }
+        from = (kv ? src_v : src_k) + layer_off + so + (size_t)part * 16;
+        to = (kv ? dst_v : dst_k) + layer_off + dof + (size_t)part * 16;
+    };
+    for (int u0 = t; u0 < total; u0 += 256 * 8) {
+        uint4 val[8];
+        uint8_t *to[8];
+#pragma unroll
+        for (int x = 0; x < 8; x++) {
+            const int u = u0 + x * 256;
+            if (u < total) {
+                const uint8_t *from;
+                locate(u, from, to[x]);
+                val[x] = *reinterpret_cast<const uint4 *>(from);
+            }
+        }
+#pragma unroll
+        for (int x = 0; x < 8; x++)
+            if (u0 + x * 256 < total) *reinterpret_cast<uint4 *>(to[x]) = val[x];
+    }
+}
+
+static int32_t check_cache_desc(const etv_cache_desc *h, bool need_paged) {
+    if (!h) return ETV_ERR_INVALID_ARG;
+    if (h->B < 0 || h->Hkv < 1 || h->d < 1 || h->n_layers < 1 || h->block_size < 0) return ETV_ERR_INVALID_ARG;
+    if (h->elem_bytes != 2 && h->elem_bytes != 4) return ETV_ERR_UNSUPPORTED;
+    if (((size_t)h->d * h->elem_bytes) % 16 != 0) return ETV_ERR_UNSUPPORTED;
+    if (need_paged && h->block_size == 0) return ETV_ERR_UNSUPPORTED;
+    if (h->block_size > 0 && (h->max_blocks < 1 || h->num_blocks < 1)) return ETV_ERR_INVALID_ARG;
+    if (h->block_size == 0 && h->P_cap < 1) return ETV_ERR_INVALID_ARG;
+    if (h->cache_layer_stride < 0 || ((size_t)h->cache_layer_stride * h->elem_bytes) % 16 != 0) return ETV_ERR_INVALID_ARG;
+    if (h->B > 65535 || h->n_layers > 65535) return ETV_ERR_UNSUPPORTED;
+    return ETV_OK;
+}
+
+}  // namespace etv
+
+extern "C" int32_t etv_replicate_branches(const etv_cache_desc *h, void *k_cache, void *v_cache,
+                                          const int32_t *block_table, const int32_t *prefix_len,
+                                          const int32_t *tail_len, int32_t N, const int32_t *free_blocks,
+                                          int32_t n_free, int32_t *branch_table, int32_t *block_base,
+                                          int32_t *n_taken, int32_t *status, void *stream) {
+    int32_t rc = etv::check_cache_desc(h, true);
+    if (rc != ETV_OK) return rc;
+    if (!n_taken || N < 1 || n_free < 0 || (n_free > 0 && !free_blocks)) return ETV_ERR_INVALID_ARG;
+    // an empty batch needs nothing but n_taken: the scan alone runs and writes 0
+    if (h->B > 0 && (!k_cache || !v_cache || !block_table || !prefix_len || !tail_len || !branch_table || !block_base ||
+                     !status))
+        return ETV_ERR_INVALID_ARG;
+    if ((((uintptr_t)k_cache) | ((uintptr_t)v_cache)) & 15) return ETV_ERR_INVALID_ARG;
+    if ((long)h->B * N * h->max_blocks > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;   // block_base is an int32
+    hipStream_t s = etv::as_stream(stream);
+    if (h->B > 0) {
+        hipLaunchKernelGGL(etv::replicate_check_kernel, dim3(h->B), dim3(256), 0, s, *h, block_table, prefix_len,
+                           tail_len, block_base, status);
+        rc = etv::check_launch();
+        if (rc != ETV_OK) return rc;
+    }
+    hipLaunchKernelGGL(etv::replicate_scan_kernel, dim3(1), dim3(256), 0, s, h->B, N, n_free, block_base, n_taken, status);
+    rc = etv::check_launch();
+    if (rc != ETV_OK || h->B == 0) return rc;
+    hipLaunchKernelGGL(etv::replicate_fill_kernel, dim3(N, h->B, h->n_layers), dim3(256), 0, s, *h,
+                       static_cast<uint8_t *>(k_cache), static_cast<uint8_t *>(v_cache), block_table, prefix_len,
+                       tail_len, N, free_blocks, block_base, branch_table, status);
+    return etv::check_launch();
+}
+
+extern "C" int32_t etv_commit_path_indices(const etv_cache_desc *h, const void *src_k, const void *src_v, void *dst_k,
+                                           void *dst_v, const int32_t *src_table, int32_t *dst_table,
+                                           const int32_t *path_indices, int32_t L_cap, const int32_t *src_len,
+                                           const int32_t *new_len, int32_t fast, int32_t *kept_len, int32_t *status,
+                                           void *stream) {
+    int32_t rc = etv::check_cache_desc(h, false);
+    if (rc != ETV_OK) return rc;
+    if (h->B == 0) return ETV_OK;
+    if (!src_k || !src_v || !dst_k || !dst_v || !path_indices || !src_len || !new_len || !kept_len || !status)
+        return ETV_ERR_INVALID_ARG;
+    if (L_cap < 1) return ETV_ERR_INVALID_ARG;
+    const bool paged = h->block_size > 0;
+    if (paged != (src_table != nullptr) || paged != (dst_table != nullptr)) return ETV_ERR_INVALID_ARG;
+    if (paged && src_table == dst_table) return ETV_ERR_INVALID_ARG;
+    if (!paged && (src_k == dst_k || src_v == dst_v)) return ETV_ERR_INVALID_ARG;   // a contiguous cache is rebuilt elsewhere
+    if ((((uintptr_t)src_k) | ((uintptr_t)src_v) | ((uintptr_t)dst_k) | ((uintptr_t)dst_v)) & 15) return ETV_ERR_INVALID_ARG;
+    hipStream_t s = etv::as_stream(stream);
+    hipLaunchKernelGGL(etv::path_commit_plan_kernel, dim3(h->B), dim3(256), 0, s, *h, src_table, dst_table,
+                       path_indices, L_cap, src_len, new_len, fast, kept_len, status);
+    rc = etv::check_launch();
+    if (rc != ETV_OK) return rc;
+    const int R = paged ? h->block_size : 16;
+    const long cap = paged ? (long)h->max_blocks * h->block_size : h->P_cap;
+    const long rows = L_cap < cap ? L_cap : cap;
+    hipLaunchKernelGGL(etv::path_commit_gather_kernel, dim3((unsigned)((rows + R - 1) / R), h->B, h->n_layers), dim3(256),
+                       0, s, *h, static_cast<const uint8_t *>(src_k), static_cast<const uint8_t *>(src_v),
+                       static_cast<uint8_t *>(dst_k), static_cast<uint8_t *>(dst_v), src_table, dst_table, path_indices,
+                       L_cap, new_len, kept_len, status);
+    return etv::check_launch();
+}
