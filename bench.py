@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--kv-split", type=int, default=0)
     ap.add_argument("--attn-flags", type=int, default=0)
     ap.add_argument("--no-lm-head", action="store_true", help="skip the timing of the fused head + argmax kernel")
+    ap.add_argument("--no-branch-cache", action="store_true",
+                    help="skip the timing of branch replication and the commit by path indices")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one device copy of this many MiB (a known-size kernel to calibrate profiler byte counters)")
     ap.add_argument("--sets", type=int, default=0, help="cache sets to rotate over (0 = enough to exceed 640 MB)")
@@ -332,6 +334,70 @@ def main():
                 "frac_of_peak_weight_pass_only": 2 * V * Dm / (pass_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
         del packed
 
+
+    # beside the step as well: the branch-cache calls on a paged pool of 7B-class shape (8 KV heads, d = 128, bf16,
+    # all layers): copy-on-write replication into N branches, the commit by path indices with the prefix shared
+    # (the common case) and as the general full reorder (every row moved: an HBM copy)
+    branch = None
+    if not a.no_branch_cache:
+        Bb, Nb, Pb, Tb, Hb, db, bsz, Lb = 8, 4, 2040, 60, 8, 128, 16, a.layers
+        per_seq = -(-(Pb + Tb) // bsz)
+        nblk = Bb * per_seq * 2 + Bb * Nb * 8 + 64
+        gen = torch.Generator(device="cuda:0").manual_seed(7)
+        pool_k = torch.empty((Lb, nblk, Hb, bsz, db), dtype=torch.bfloat16, device="cuda:0").normal_(generator=gen)
+        pool_v = torch.empty_like(pool_k).normal_(generator=gen)
+        ids = torch.randperm(nblk, generator=torch.Generator().manual_seed(7)).to(torch.int32)
+        table = ids[: Bb * per_seq].reshape(Bb, per_seq).contiguous().to("cuda:0")
+        free = ids[Bb * per_seq:].contiguous().to("cuda:0")
+        plen = torch.full((Bb,), Pb, dtype=torch.int32, device="cuda:0")
+        tlen = torch.full((Bb,), Tb, dtype=torch.int32, device="cuda:0")
+
+        def timed(fn, n=20):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / n
+        rep = api.replicate_branches(pool_k, pool_v, table, plen, tlen, Nb, free)
+        assert int(rep["status"].abs().sum().item()) == 0
+        taken = int(rep["n_taken"].item())
+        # each call is captured in a HIP graph like the step, so the figures are device time, not the binding's
+        g_rep = st.capture(lambda: api.replicate_branches(pool_k, pool_v, table, plen, tlen, Nb, free))
+        repl_us = timed(g_rep.replay)
+        src_t = rep["branch_table"][:, 1].contiguous()
+        dst_t = torch.full_like(src_t, -1)
+        dst_t[:, :per_seq] = free[taken: taken + Bb * per_seq].reshape(Bb, per_seq)
+        Ln = Pb + 6                                    # the root and five accepted draft tokens
+        pidx = torch.arange(Ln, dtype=torch.int32).repeat(Bb, 1)
+        pidx[:, Pb:] = Pb + torch.tensor([0, 2, 7, 19, 33, 51], dtype=torch.int32)
+        pidx = pidx.to("cuda:0")
+        slen = torch.full((Bb,), Pb + Tb, dtype=torch.int32, device="cuda:0")
+        nlen = torch.full((Bb,), Ln, dtype=torch.int32, device="cuda:0")
+        keep_t = dst_t.clone()
+
+        def path_commit(fast):
+            dst_t.copy_(keep_t)
+            return api.commit_path_indices(pool_k, pool_v, pool_k, pool_v, pidx, slen, nlen, src_table=src_t,
+                                           dst_table=dst_t, fast=fast)
+        r = path_commit(True)
+        assert int(r["status"].abs().sum().item()) == 0 and int(r["kept_len"][0].item()) == Pb // bsz * bsz
+        g_tab, g_fast = st.capture(lambda: dst_t.copy_(keep_t)), st.capture(lambda: path_commit(True))
+        g_full = st.capture(lambda: path_commit(False))
+        table_us = timed(g_tab.replay)                 # restoring the destination table is not part of the call
+        fast_us = timed(g_fast.replay) - table_us
+        full_us = timed(g_full.replay, n=5) - table_us
+        moved = 2 * 2 * Ln * Hb * db * 2 * Lb * Bb       # read + write, K and V, every row, every layer, every sequence
+        branch = {"shape": f"B={Bb} N={Nb} P={Pb} T={Tb} Hkv={Hb} d={db} bf16 block={bsz} layers={Lb}",
+                  "replicate_us": repl_us, "deep_copy_bytes_avoided": 2 * Pb * Hb * db * 2 * Lb * Bb * Nb,
+                  "commit_path_indices_fast_us": fast_us, "commit_path_indices_full_reorder_us": full_us,
+                  "full_reorder_bytes": moved, "full_reorder_hbm_gbs": moved / (full_us * 1e-6) / 1e9,
+                  "full_reorder_frac_of_peak": moved / (full_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        del pool_k, pool_v
+
     cpu = None if a.skip_cpu else cpu_baseline(a.workload, a.layers)
     line = {
         "metric": "tree-verify tokens/s (batch x tree nodes)", "value": tokens_per_step / (ms_per_step * 1e-3),
@@ -340,7 +406,7 @@ def main():
         "config": {"workload": f"{a.workload}: {desc_text}", "layers": a.layers, "tokens_per_step": tokens_per_step,
                    "launch": "eager" if a.no_graph else "hip-graph replay", "cache_sets": st.nsets,
                    "cache_bytes": st.cache_bytes, "kv_split": a.kv_split},
-        "roofline": roof, "cpu_baseline": cpu, "lm_head_argmax": head,
+        "roofline": roof, "cpu_baseline": cpu, "lm_head_argmax": head, "branch_cache": branch,
     }
     print(json.dumps(line))
 

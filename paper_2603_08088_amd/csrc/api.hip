@@ -6,18 +6,20 @@ thread_local int32_t g_last_hip_error = 0;
 }
 
 namespace etv {
-// Streaming read of a buffer with 16-byte loads, 8 in flight per lane: what plain loads achieve on this
-// machine, the practical ceiling for the K/V streaming of the attention kernel.
-__global__ void __launch_bounds__(256) hbm_read_probe_kernel(const uint4 *__restrict__ src, size_t n16, uint4 *sink) {
+// Streaming read of a buffer with 16-byte nontemporal loads, 8 in flight per lane: what a read-once stream
+// achieves on this machine (7.1 TB/s; plain loads that allocate in L2 reach 6.0-6.4 TB/s), the practical ceiling
+// for the K/V streaming of the attention kernel.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256) hbm_read_probe_kernel(const u32x4 *__restrict__ src, size_t n16, u32x4 *sink) {
     const size_t per_wg = n16 / gridDim.x;
-    const uint4 *p = src + per_wg * blockIdx.x;
-    uint4 acc = {0, 0, 0, 0};
+    const u32x4 *p = src + per_wg * blockIdx.x;
+    u32x4 acc = {0, 0, 0, 0};
     for (size_t i = threadIdx.x; i + 7 * 256 < per_wg; i += 256 * 8) {
-        uint4 v[8];
+        u32x4 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; u++) v[u] = p[i + u * 256];
+        for (int u = 0; u < 8; u++) v[u] = __builtin_nontemporal_load(p + i + u * 256);
 #pragma unroll
-        for (int u = 0; u < 8; u++) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+        for (int u = 0; u < 8; u++) acc ^= v[u];
     }
     if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u && acc.z == 0x0fedcba9u) sink[0] = acc;  // keeps the loads alive
 }
@@ -26,7 +28,7 @@ __global__ void __launch_bounds__(256) hbm_read_probe_kernel(const uint4 *__rest
 extern "C" int32_t etv_hbm_read_probe(const void *buf, size_t bytes, void *sink, void *stream) {
     if (!buf || !sink || bytes < (size_t)1 << 20 || ((uintptr_t)buf & 15) || ((uintptr_t)sink & 15)) return ETV_ERR_INVALID_ARG;
     hipLaunchKernelGGL(etv::hbm_read_probe_kernel, dim3(4096), dim3(256), 0, etv::as_stream(stream),
-                       static_cast<const uint4 *>(buf), bytes / 16, static_cast<uint4 *>(sink));
+                       static_cast<const etv::u32x4 *>(buf), bytes / 16, static_cast<etv::u32x4 *>(sink));
     return etv::check_launch();
 }
 

@@ -5,6 +5,8 @@
 
 namespace etv {
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte unit the streaming builtins accept
+
 // --------------------------------------------------------------------------------------------------------------
 // replicate_branches
 // --------------------------------------------------------------------------------------------------------------
@@ -105,6 +107,10 @@ __global__ void __launch_bounds__(256) replicate_fill_kernel(etv_cache_desc dsc,
         const int blk = free_blocks[base + x];
         bad |= (blk < 0 || blk >= dsc.num_blocks);
     }
+    // looked up ahead of the barrier so that the copy below does not start with another trip to memory
+    const int rows = st ? 0 : P - rn.first * bs;   // committed rows inside the partly filled block
+    const int src_blk = rows > 0 ? block_table[(size_t)b * dsc.max_blocks + rn.first] : 0;
+    const int dst_blk = rows > 0 ? free_blocks[base + (size_t)i * rn.need] : 0;
     const bool bad_free = __syncthreads_or(bad) != 0;
     const bool failed = st != 0 || bad_free;
     const int32_t *mine = free_blocks + base + (size_t)i * rn.need;
@@ -117,9 +123,7 @@ __global__ void __launch_bounds__(256) replicate_fill_kernel(etv_cache_desc dsc,
             row[k] = v;
         }
     }
-    const int rows = P - rn.first * bs;   // committed rows inside the partly filled block
     if (failed || rows <= 0) return;
-    const int src_blk = block_table[(size_t)b * dsc.max_blocks + rn.first], dst_blk = mine[0];
     const size_t head_bytes = (size_t)dsc.d * dsc.elem_bytes;
     const int upr = (int)(head_bytes / 16);              // 16-byte units per row of one head
     const int per_head = rows * upr;                     // the rows of a head are consecutive memory
@@ -131,7 +135,8 @@ __global__ void __launch_bounds__(256) replicate_fill_kernel(etv_cache_desc dsc,
         uint8_t *cache = (is_v ? v_cache : k_cache) + layer_off;
         const size_t so = ((size_t)src_blk * dsc.Hkv + hh) * bs * head_bytes + (size_t)w * 16;
         const size_t dof = ((size_t)dst_blk * dsc.Hkv + hh) * bs * head_bytes + (size_t)w * 16;
-        *reinterpret_cast<uint4 *>(cache + dof) = *reinterpret_cast<const uint4 *>(cache + so);
+        __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(cache + so)),
+                                    reinterpret_cast<u32x4 *>(cache + dof));
     }
 }
 
@@ -190,10 +195,18 @@ __global__ void __launch_bounds__(256) path_commit_plan_kernel(etv_cache_desc ds
         for (int k = t; k < keep / bs; k += 256) dst_table[(size_t)b * dsc.max_blocks + k] = src_table[(size_t)b * dsc.max_blocks + k];
 }
 
-// grid (row chunks, B, n_layers), 256 threads.  A chunk is one destination block (paged) or 16 rows (contiguous);
-// its rows j in [kept_len, new_len) are copied from source row path_indices[j], K and V, all heads.  Units of 16
-// bytes are numbered so that consecutive lanes write consecutive memory: (K|V, head, row, part) in a block,
-// (K|V, row, head, part) in a contiguous cache.  Eight loads are issued before their stores.
+// grid (X, B, n_layers), 256 threads.  A chunk is one destination block (paged) or 16 rows (contiguous); workgroup x
+// takes the chunks first + x, first + x + X, ... where first is the chunk that holds row kept_len, so a call that
+// keeps the prefix can use a small grid whatever the prefix length.  The rows j in [kept_len, new_len) of a chunk
+// are copied from source row path_indices[j], K and V, all heads.  A row consists of pieces of consecutive memory
+// (one per K|V and head in a block, one per K|V in a contiguous cache); a thread owns the same 16-byte unit of
+// every piece of its row, so consecutive lanes write consecutive memory and the per-row lookups (index, source
+// block) are done once, ahead of the copies.  A batch is VB row positions x SB pieces = 8 loads, all issued
+// before their stores; lanes past the end of the chunk load a clamped (valid) address and store nothing, so the
+// batch is straight-line code and no load waits for another.  Loads and stores are streaming (nontemporal): every
+// byte is touched once, and plain stores left in L2 for the write-back at the end of the kernel cost a quarter of
+// the bandwidth of a full reorder and half the time of a short one.
+template <bool PAGED>
 __global__ void __launch_bounds__(256) path_commit_gather_kernel(etv_cache_desc dsc, const uint8_t *src_k,
                                                                  const uint8_t *src_v,
                                                                  uint8_t *dst_k, uint8_t *dst_v,
@@ -203,55 +216,75 @@ __global__ void __launch_bounds__(256) path_commit_gather_kernel(etv_cache_desc 
                                                                  const int32_t *__restrict__ new_len,
                                                                  const int32_t *__restrict__ kept_len,
                                                                  const int32_t *__restrict__ status) {
+    constexpr int VB = PAGED ? 1 : 4, SB = 8 / VB;
     const int b = blockIdx.y, l = blockIdx.z, t = threadIdx.x;
+    const int keep = kept_len[b], Ln = new_len[b];
     if (status[b]) return;
     const int bs = dsc.block_size;
-    const bool paged = bs > 0;
-    const int R = paged ? bs : 16;
-    const int j0 = blockIdx.x * R;
-    const int lo = max(j0, kept_len[b]), hi = min(j0 + R, new_len[b]);
-    if (lo >= hi) return;
+    const int R = PAGED ? bs : 16;
     const size_t head_bytes = (size_t)dsc.d * dsc.elem_bytes;
-    const int upr = (int)(head_bytes / 16);
     const int Hkv = dsc.Hkv;
+    const int width = (int)(head_bytes / 16) * (PAGED ? 1 : Hkv);   // 16-byte units of one piece
+    const int slabs = PAGED ? 2 * Hkv : 2;                          // pieces per row: (K|V, head) or (K|V)
+    const size_t piece_stride = PAGED ? (size_t)bs * head_bytes : 0;
+    const int wsh = (width & (width - 1)) == 0 ? __ffs(width) - 1 : -1;
     const size_t layer_off = (size_t)l * (size_t)dsc.cache_layer_stride * dsc.elem_bytes;
     const int32_t *idx = path_indices + (size_t)b * L_cap;
-    const int32_t *srow = paged ? src_table + (size_t)b * dsc.max_blocks : nullptr;
-    const int dst_blk = paged ? dst_table[(size_t)b * dsc.max_blocks + blockIdx.x] : 0;
-    const int nrow = hi - lo;
-    const int total = 2 * Hkv * nrow * upr;
-    auto locate = [&](int u, const uint8_t *&from, uint8_t *&to) {
-        const int part = u % upr;
-        int q = u / upr, r, hh, kv;
-        if (paged) { r = q % nrow; q /= nrow; hh = q % Hkv; kv = q / Hkv; }
-        else       { hh = q % Hkv; q /= Hkv; r = q % nrow; kv = q / nrow; }
-        const int j = lo + r, sj = idx[j];
-        size_t so, dof;
-        if (paged) {
-            so = (((size_t)srow[sj / bs] * Hkv + hh) * bs + sj % bs) * head_bytes;
-            dof = (((size_t)dst_blk * Hkv + hh) * bs + (j - j0)) * head_bytes;
-        } else {
-            so = (((size_t)b * dsc.P_cap + sj) * Hkv + hh) * head_bytes;
-            dof = (((size_t)b * dsc.P_cap + j) * Hkv + hh) * head_bytes;
-        }
-        from = (kv ? src_v : src_k) + layer_off + so + (size_t)part * 16;
-        to = (kv ? dst_v : dst_k) + layer_off + dof + (size_t)part * 16;
-    };
-    for (int u0 = t; u0 < total; u0 += 256 * 8) {
-        uint4 val[8];
-        uint8_t *to[8];
+    const int32_t *srow = PAGED ? src_table + (size_t)b * dsc.max_blocks : nullptr;
+    for (int c = keep / R + blockIdx.x; c * R < Ln; c += gridDim.x) {
+        const int j0 = c * R;
+        const int lo = max(j0, keep), hi = min(j0 + R, Ln);
+        const int dst_blk = PAGED ? dst_table[(size_t)b * dsc.max_blocks + c] : 0;
+        const int per = (hi - lo) * width;             // units of one piece over the chunk's rows
+        for (int v0 = 0; v0 < per; v0 += 256 * VB) {
+            size_t so[VB], dof[VB];
+            bool live[VB];
+            int sj[VB];
 #pragma unroll
-        for (int x = 0; x < 8; x++) {
-            const int u = u0 + x * 256;
-            if (u < total) {
-                const uint8_t *from;
-                locate(u, from, to[x]);
-                val[x] = *reinterpret_cast<const uint4 *>(from);
+            for (int y = 0; y < VB; y++) {
+                const int v = v0 + y * 256 + t;
+                live[y] = v < per;
+                const int vc = live[y] ? v : per - 1;
+                const int r = wsh >= 0 ? vc >> wsh : vc / width;
+                const int j = lo + r;
+                sj[y] = idx[j];
+                dof[y] = (size_t)(vc - r * width) * 16 +
+                         (PAGED ? ((size_t)dst_blk * Hkv * bs + (j - j0)) * head_bytes
+                                : ((size_t)b * dsc.P_cap + j) * Hkv * head_bytes);
+                so[y] = (size_t)(vc - r * width) * 16;
+            }
+#pragma unroll
+            for (int y = 0; y < VB; y++) {
+                if (PAGED) {
+                    const int sb = sj[y] / bs;
+                    so[y] += ((size_t)srow[sb] * Hkv * bs + (sj[y] - sb * bs)) * head_bytes;
+                } else {
+                    so[y] += ((size_t)b * dsc.P_cap + sj[y]) * Hkv * head_bytes;
+                }
+            }
+            for (int s0 = 0; s0 < slabs; s0 += SB) {
+                u32x4 val[VB][SB];
+#pragma unroll
+                for (int x = 0; x < SB; x++) {
+                    const int slab = min(s0 + x, slabs - 1);   // uniform; a repeated piece is loaded, not stored
+                    const int kv = slab >= slabs / 2;
+                    const size_t within = layer_off + (size_t)(slab - kv * (slabs / 2)) * piece_stride;
+#pragma unroll
+                    for (int y = 0; y < VB; y++)
+                        val[y][x] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>((kv ? src_v : src_k) + within + so[y]));
+                }
+#pragma unroll
+                for (int x = 0; x < SB; x++) {
+                    const int slab = s0 + x;
+                    if (slab >= slabs) break;
+                    const int kv = slab >= slabs / 2;
+                    const size_t within = layer_off + (size_t)(slab - kv * (slabs / 2)) * piece_stride;
+#pragma unroll
+                    for (int y = 0; y < VB; y++)
+                        if (live[y]) __builtin_nontemporal_store(val[y][x], reinterpret_cast<u32x4 *>((kv ? dst_v : dst_k) + within + dof[y]));
+                }
             }
         }
-#pragma unroll
-        for (int x = 0; x < 8; x++)
-            if (u0 + x * 256 < total) *reinterpret_cast<uint4 *>(to[x]) = val[x];
     }
 }
 
@@ -324,7 +357,13 @@ extern "C" int32_t etv_commit_path_indices(const etv_cache_desc *h, const void *
     const int R = paged ? h->block_size : 16;
     const long cap = paged ? (long)h->max_blocks * h->block_size : h->P_cap;
     const long rows = L_cap < cap ? L_cap : cap;
-    hipLaunchKernelGGL(etv::path_commit_gather_kernel, dim3((unsigned)((rows + R - 1) / R), h->B, h->n_layers), dim3(256),
+    const long chunks = (rows + R - 1) / R;
+    // a full reorder gets a workgroup per chunk; a call that expects to keep the prefix gets a few per sequence and
+    // layer, which loop over the chunks if the indices turn out not to preserve it
+    long X = (fast && paged) ? 4 : chunks;
+    X = X > chunks ? chunks : X;
+    auto kern = paged ? etv::path_commit_gather_kernel<true> : etv::path_commit_gather_kernel<false>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)X, h->B, h->n_layers), dim3(256),
                        0, s, *h, static_cast<const uint8_t *>(src_k), static_cast<const uint8_t *>(src_v),
                        static_cast<uint8_t *>(dst_k), static_cast<uint8_t *>(dst_v), src_table, dst_table, path_indices,
                        L_cap, new_len, kept_len, status);

@@ -37,9 +37,11 @@ __global__ void __launch_bounds__(256) argmax_partial_kernel(const float *__rest
     const int end = min(V, begin + kChunk);
     MaxIdx m = {-INFINITY, 0x7fffffff};
     if ((V & 3) == 0 && (((uintptr_t)logits) & 15) == 0) {
-        const float4 *row4 = reinterpret_cast<const float4 *>(row);
+        // streaming loads: every logit is read once
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        const f32x4 *row4 = reinterpret_cast<const f32x4 *>(row);
         for (int i = begin / 4 + threadIdx.x; i < end / 4; i += 256) {
-            float4 x = row4[i];
+            const f32x4 x = __builtin_nontemporal_load(row4 + i);
             int base = i * 4;
             // ascending index order with strict '>' keeps the lowest index among equals
             if (x.x > m.v || m.i == 0x7fffffff) m = {x.x, base};
