@@ -135,8 +135,7 @@ __global__ void __launch_bounds__(256) replicate_fill_kernel(etv_cache_desc dsc,
         uint8_t *cache = (is_v ? v_cache : k_cache) + layer_off;
         const size_t so = ((size_t)src_blk * dsc.Hkv + hh) * bs * head_bytes + (size_t)w * 16;
         const size_t dof = ((size_t)dst_blk * dsc.Hkv + hh) * bs * head_bytes + (size_t)w * 16;
-        __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(cache + so)),
-                                    reinterpret_cast<u32x4 *>(cache + dof));
+        *reinterpret_cast<uint4 *>(cache + dof) = *reinterpret_cast<const uint4 *>(cache + so);   // plain: streaming ones were slower here
     }
 }
 
