@@ -287,7 +287,7 @@ ETV_API int32_t etv_commit_accepted_kv(const etv_commit_desc *h_desc, const void
  *  maxval   out float [B, T_max]       the maximal logit, -inf for padded rows     nullable
  *  workspace: etv_lm_head_argmax_workspace_bytes(B, T_max, V) bytes.
  * Requires D % 128 == 0.  Built for the row counts of a verify step (B * T_max up to a few
- * hundred): every group of 64 rows streams the weights once (repeats come from L2).
+ * hundred): up to 64 rows, and every group of 128 rows beyond that, stream the weights once (repeats come from L2).
  * ------------------------------------------------------------------------- */
 ETV_API size_t etv_lm_head_argmax_workspace_bytes(int32_t B, int32_t T_max, int32_t V);
 

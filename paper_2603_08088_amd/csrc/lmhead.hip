@@ -11,8 +11,17 @@
 // C^T[vocab, node] = W . H^T on v_mfma_f32_32x32x16_bf16: A = weight rows, B = hidden rows, so a node is an
 // accumulator column and its maximum over the vocabulary stays in one lane pair.  The 16-byte chunk c of tile
 // row r sits at chunk position c ^ (r & 15), which spreads the fragment reads of 32 consecutive rows over the
-// LDS banks.  More than 64 rows run as further row groups: they stream the weights again, placed so that the
-// groups of one vocabulary tile share an XCD and the repeat comes from its L2.
+// LDS banks.
+//
+// More than 64 rows (lm_head_argmax_wide_kernel): a workgroup takes up to 128 node rows.  What bounds the stream is
+// the weight bytes a compute unit keeps in flight (in flight / latency = rate), so LDS is spent on weights: a step
+// is half a weight tile (64 vocabulary rows x 256 B = 16 KiB, consecutive in the packed layout) in a ring of five
+// stages, and the 128 hidden rows of a contraction step (32 KiB, from L2) serve both halves and get a ring of two.
+// A wavefront's loads complete in order, so the deep weight ring and the shallow hidden ring are fed by different
+// wavefronts (0..3 weights, 4..7 hidden rows), each waiting on its own counter.  Wavefront w owns vocabulary block
+// w % 2 of each half and node chunk w / 2, with one accumulator per half.  More than 128 rows run as further row
+// groups: they stream the weights again, placed so that the groups of one vocabulary tile share an XCD and the
+// repeat comes from its L2.
 //
 // Weight layout.  With row-major [V, D] weights a step reads 128 pieces of 256 B that lie 2 * D bytes apart,
 // and the stream reaches 4.6-4.8 TB/s; with the weights packed once into tiles ([V/128][D/128][128 rows][128],
@@ -38,7 +47,14 @@ extern __shared__ __attribute__((aligned(1024))) uint8_t lh_smem[];
 // NT: streaming (nontemporal) load, for bytes that no other workgroup will ask for: they stream a seventh faster
 // than plain loads on this machine, but do not stay in L2.
 template <bool NT>
-__device__ __forceinline__ void lh_async_load16(const void *sbase, uint32_t voff, uint32_t lds_addr) {
+__device__ __forceinline__ void lh_async_load16(const void *sbase_in, uint32_t voff, uint32_t lds_addr_in) {
+    // base and LDS address are the same in every lane; readfirstlane says so to the compiler whatever it concluded
+    // about the selects and loops they came through (it folds away for values already in scalar registers)
+    const uint64_t raw = (uint64_t)(uintptr_t)sbase_in;
+    const uint64_t uni = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(raw >> 32)) << 32) |
+                         (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)raw);
+    const void *sbase = (const void *)(uintptr_t)uni;
+    const uint32_t lds_addr = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_addr_in);
     if (NT)
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt\n" ::"v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
     else
@@ -219,6 +235,227 @@ __global__ void __launch_bounds__(512, 1) lm_head_argmax_kernel(LhParams p) {
     }
 }
 
+// ----------------------------------------------------------------------------------------------------------------
+// 65..128 node rows per workgroup (see the file comment).  Step s = (contraction step k = s / 2, tile half s % 2).
+// ----------------------------------------------------------------------------------------------------------------
+constexpr int LHW_RT = 128;                  // node rows per workgroup
+constexpr int LHW_W_STEP = 64 * LH_ROWB;     // 16 KiB: 64 vocabulary rows of a step
+constexpr int LHW_H_STEP = LHW_RT * LH_ROWB; // 32 KiB: the hidden rows of a contraction step
+constexpr int LHW_NSW = 5, LHW_NSH = 2;      // ring stages: weights, hidden rows
+constexpr int LHW_W_RING = LHW_NSW * LHW_W_STEP;
+static_assert(LHW_W_RING + LHW_NSH * LHW_H_STEP == LH_NS * LH_STAGE, "both kernels use the same 144 KiB");
+
+__global__ void __launch_bounds__(512, 1) lm_head_argmax_wide_kernel(LhParams p) {
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lh_smem;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c32 = lane & 31, hh = lane >> 5;
+    const int rest = blockIdx.x >> 3;
+    const int group = rest % p.groups;
+    const int tile = (rest / p.groups) * 8 + (blockIdx.x & 7);
+    if (tile >= p.tiles) return;  // uniform over the workgroup
+    const int v0 = tile * LH_VT;
+    const int r0 = group * LHW_RT;
+    const int nrows = min(LHW_RT, p.rows_total - r0);   // >= 1
+    const int nchunks = (nrows + 31) >> 5;
+    const int ksteps = p.D / LH_KC;
+    const int steps = 2 * ksteps;
+
+    // Loads: 1 KiB units of 4 rows x 256 B as in the narrow kernel.  Issuing wavefront iw (of four per kind) takes
+    // units iw, iw + 4, ...: the row within the tile is 4 * unit + i / 16, so row & 15 = (4 * iw + i / 16) & 15.
+    const bool w_issuer = wave < 4;
+    const int iw = wave & 3;
+    const int l_row = lane >> 4;
+    const uint32_t lane_col = (uint32_t)(((lane & 15) ^ ((4 * iw + l_row) & 15)) * 16);
+    const size_t row_bytes = (size_t)p.D * 2;
+    // weights: 16 units per step, 4 per issuing wavefront; row-major sources differ between the two tile halves
+    uint32_t wvoff[2][4];
+    const uint8_t *wbase[2][4];
+#pragma unroll
+    for (int h = 0; h < 2; h++)
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int unit = iw + 4 * u;
+            if (p.packed) {  // the tile's bytes in step order: step s at s * 16 KiB
+                wbase[h][u] = p.weight + (size_t)tile * ksteps * LH_W_BYTES + (size_t)unit * 1024;
+                wvoff[h][u] = (uint32_t)(l_row * LH_ROWB) + lane_col;
+            } else {
+                const int vrow = min(v0 + 64 * h + 4 * unit + l_row, p.V - 1);
+                const int vfirst = min(v0 + 64 * h + 4 * unit, p.V - 1);
+                wbase[h][u] = p.weight + (size_t)vfirst * row_bytes;
+                wvoff[h][u] = (uint32_t)((size_t)(vrow - vfirst) * row_bytes) + lane_col;
+            }
+        }
+    // hidden rows: 32 units per contraction step, 8 per issuing wavefront
+    uint32_t hvoff[8];
+    const uint8_t *hbase[8];
+    bool h_on[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) {
+        const int unit = iw + 4 * u;
+        const int last = r0 + nrows - 1;
+        const int rrow = min(r0 + 4 * unit + l_row, last);
+        const int rfirst = min(r0 + 4 * unit, last);
+        hbase[u] = p.hidden + (size_t)rfirst * row_bytes;
+        hvoff[u] = (uint32_t)((size_t)(rrow - rfirst) * row_bytes) + lane_col;
+        h_on[u] = 4 * unit < nrows;
+    }
+    auto issue_w = [&](int s) {
+        const uint32_t dst = smem_addr + (uint32_t)(s % LHW_NSW) * LHW_W_STEP + (uint32_t)iw * 1024;
+        const int h = s & 1;
+        const size_t off = p.packed ? (size_t)s * LHW_W_STEP : (size_t)(s >> 1) * LH_ROWB;
+        if (p.groups == 1) {   // one reader per weight byte: streamed
+#pragma unroll
+            for (int u = 0; u < 4; u++) lh_async_load16<true>(wbase[h][u] + off, wvoff[h][u], dst + u * 4096);
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; u++) lh_async_load16<false>(wbase[h][u] + off, wvoff[h][u], dst + u * 4096);
+        }
+    };
+    auto issue_h = [&](int k) {
+        const uint32_t dst = smem_addr + LHW_W_RING + (uint32_t)(k % LHW_NSH) * LHW_H_STEP + (uint32_t)iw * 1024;
+        const size_t off = (size_t)k * LH_ROWB;
+#pragma unroll
+        for (int u = 0; u < 8; u++)
+            if (h_on[u]) lh_async_load16<false>(hbase[u] + off, hvoff[u], dst + u * 4096);
+    };
+    // prologue: fill both rings
+    if (w_issuer) {
+        for (int s = 0; s < LHW_NSW && s < steps; s++) issue_w(s);
+    } else {
+        issue_h(0);
+        if (ksteps > 1) issue_h(1);
+    }
+
+    const int vb = wave & 1, cg = wave >> 1;
+    const uint32_t a_row = (uint32_t)((32 * vb + c32) * LH_ROWB);
+    const uint32_t b_row = (uint32_t)(LHW_W_RING + (32 * cg + c32) * LH_ROWB);
+    const int sw = c32 & 15;
+    const bool has = cg < nchunks;
+    lh_f32x16 acc[2];  // one per tile half (the two wavefronts of a SIMD interleave their chains)
+#pragma unroll
+    for (int i = 0; i < 16; i++) { acc[0][i] = 0.f; acc[1][i] = 0.f; }
+
+    // Fragments are read one step ahead of the products that use them, so a wavefront's LDS reads of step s + 1
+    // run under its matrix instructions of step s.  A = the weight rows of the step, B = the hidden rows of the
+    // contraction step, read once and used for both tile halves.
+    auto read_a = [&](int s, lh_bf16x8 (&a)[8]) {
+        const uint8_t *wst = lh_smem + (s % LHW_NSW) * LHW_W_STEP + a_row;
+#pragma unroll
+        for (int kk = 0; kk < 8; kk++) a[kk] = *reinterpret_cast<const lh_bf16x8 *>(wst + (((2 * kk + hh) ^ sw) << 4));
+    };
+    auto read_b = [&](int k, lh_bf16x8 (&bf)[8]) {
+        const uint8_t *hst = lh_smem + (k % LHW_NSH) * LHW_H_STEP + b_row;
+#pragma unroll
+        for (int kk = 0; kk < 8; kk++) bf[kk] = *reinterpret_cast<const lh_bf16x8 *>(hst + (((2 * kk + hh) ^ sw) << 4));
+    };
+    auto products = [&](const lh_bf16x8 (&a)[8], const lh_bf16x8 (&bf)[8], lh_f32x16 &c) {
+#pragma unroll
+        for (int kk = 0; kk < 8; kk++) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], bf[kk], c, 0, 0, 0);
+    };
+    // Before the barrier of ring step s: this wavefront's loads of step s + 1 have landed (weights: steps s + 2 ..
+    // s + 4 may stay outstanding, four loads each; hidden rows: contraction step (s + 1) / 2 is needed from an odd
+    // s on and nothing younger is outstanding then), and its own fragment reads of step s are done.  After the
+    // barrier: step s + 1 is visible to everyone, the weight stage of step s is free (refilled with step s + 5),
+    // and on odd s so is the hidden-row stage of contraction step s / 2 (refilled with s / 2 + 2).
+    auto ring_step = [&](int s) {
+        if (w_issuer) {
+            const int ahead = min(3, steps - 2 - s);
+            if (ahead >= 3) lh_wait_vmcnt<12>();
+            else if (ahead == 2) lh_wait_vmcnt<8>();
+            else if (ahead == 1) lh_wait_vmcnt<4>();
+            else lh_wait_vmcnt<0>();
+        } else if (s & 1) {
+            lh_wait_vmcnt<0>();
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the fragment reads of step s
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (w_issuer) {
+            if (s + LHW_NSW < steps) issue_w(s + LHW_NSW);
+        } else if ((s & 1) && (s >> 1) + 2 < ksteps) {
+            issue_h((s >> 1) + 2);
+        }
+    };
+
+    lh_bf16x8 a_even[8], a_odd[8], b_cur[8], b_next[8];
+    // step 0 and contraction step 0 must be in LDS before the first fragment reads
+    if (w_issuer) {
+        const int ahead = min(LHW_NSW - 1, steps - 1);
+        if (ahead >= 4) lh_wait_vmcnt<16>();
+        else if (ahead == 3) lh_wait_vmcnt<12>();
+        else if (ahead == 2) lh_wait_vmcnt<8>();
+        else lh_wait_vmcnt<4>();
+    } else {
+        lh_wait_vmcnt<0>();
+    }
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (has) {
+        read_a(0, a_even);
+        read_b(0, b_cur);
+    }
+    for (int k = 0; k < ksteps; k++) {
+        // even step 2k: half 0
+        ring_step(2 * k);
+        if (has) {
+            read_a(2 * k + 1, a_odd);
+            products(a_even, b_cur, acc[0]);
+        }
+        // odd step 2k + 1: half 1; the next contraction step's fragments are read here
+        ring_step(2 * k + 1);
+        if (has) {
+            if (k + 1 < ksteps) {
+                read_a(2 * k + 2, a_even);
+                read_b(k + 1, b_next);
+            }
+            products(a_odd, b_cur, acc[1]);
+            if (k + 1 < ksteps) {
+#pragma unroll
+                for (int kk = 0; kk < 8; kk++) b_cur[kk] = b_next[kk];
+            }
+        }
+    }
+
+    // Epilogue as in the narrow kernel: per node column the maximum over this wavefront's 2 x 32 vocabulary rows
+    // (ascending: half 0 then half 1, element i of lane half hh is row 8 * (i / 4) + 4 * hh + i % 4), then over
+    // the two lane halves, then over the two vocabulary blocks through LDS.  Lowest index wins among equals.
+    __builtin_amdgcn_s_barrier();  // the rings are free
+    float *s_val = reinterpret_cast<float *>(lh_smem);                    // [2 blocks][128 rows]
+    int32_t *s_idx = reinterpret_cast<int32_t *>(lh_smem + 2 * LHW_RT * 4);
+    if (has) {
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int h = 0; h < 2; h++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const int v = v0 + 64 * h + 32 * vb + 8 * (i >> 2) + 4 * hh + (i & 3);
+                const float x = (v < p.V) ? acc[h][i] : -INFINITY;
+                if (x > bv || (bi == 0x7fffffff && v < p.V)) { bv = x; bi = v; }
+            }
+        const float ov = __shfl_xor(bv, 32);
+        const int oi = __shfl_xor(bi, 32);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        if (hh == 0) {
+            const int rl = 32 * cg + c32;
+            s_val[vb * LHW_RT + rl] = bv;
+            s_idx[vb * LHW_RT + rl] = bi;
+        }
+    }
+    __syncthreads();
+    if (tid < nrows) {
+        float bv = s_val[tid];
+        int bi = s_idx[tid];
+        const float ov = s_val[LHW_RT + tid];
+        const int oi = s_idx[LHW_RT + tid];
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        const size_t o = (size_t)(r0 + tid) * p.tiles + tile;
+        p.pval[o] = bv;
+        p.pidx[o] = bi;
+    }
+}
+
 // One wavefront per node row: reduce the per-tile partials (lowest index among equals); padded rows give -1.
 __global__ void __launch_bounds__(256) lm_head_finish_kernel(const float *__restrict__ pval,
                                                             const int32_t *__restrict__ pidx, int tiles,
@@ -308,7 +545,9 @@ extern "C" int32_t etv_lm_head_argmax(const void *hidden, const void *weight, in
     if ((size_t)D * 2 * 8 >= (1ull << 32)) return ETV_ERR_UNSUPPORTED;
     if (B == 0) return ETV_OK;
     const long rows_total = (long)B * T_max;
-    const long groups = (rows_total + LH_RT - 1) / LH_RT;
+    const bool wide = rows_total > LH_RT;   // more than 64 rows: 128 per workgroup
+    const long rt = wide ? LHW_RT : LH_RT;
+    const long groups = (rows_total + rt - 1) / rt;
     const long tiles = ((long)V + LH_VT - 1) / LH_VT;
     if (groups > 65535 || rows_total > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < etv_lm_head_argmax_workspace_bytes(B, T_max, V))
@@ -324,13 +563,16 @@ extern "C" int32_t etv_lm_head_argmax(const void *hidden, const void *weight, in
     constexpr size_t lds = (size_t)LH_NS * LH_STAGE;
     static const bool lds_ok = [] {
         return hipFuncSetAttribute(reinterpret_cast<const void *>(&lm_head_argmax_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess &&
+               hipFuncSetAttribute(reinterpret_cast<const void *>(&lm_head_argmax_wide_kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
     }();
     if (!lds_ok) return ETV_ERR_HIP;
     hipStream_t s = as_stream(stream);
     const long nblocks = ((tiles + 7) / 8) * groups * 8;
     if (nblocks > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(lm_head_argmax_kernel, dim3((unsigned)nblocks), dim3(512), lds, s, p);
+    if (wide) hipLaunchKernelGGL(lm_head_argmax_wide_kernel, dim3((unsigned)nblocks), dim3(512), lds, s, p);
+    else hipLaunchKernelGGL(lm_head_argmax_kernel, dim3((unsigned)nblocks), dim3(512), lds, s, p);
     int32_t rc = check_launch();
     if (rc != ETV_OK || !argmax) return rc;  // without argmax the per-tile maxima stay in the workspace for the epilogue
     hipLaunchKernelGGL(lm_head_finish_kernel, dim3((unsigned)((rows_total + 3) / 4)), dim3(256), 0, s, p.pval, p.pidx,

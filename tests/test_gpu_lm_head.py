@@ -58,7 +58,8 @@ def _check(h_bits, w_bits, n, exact=None):
 
 @pytest.mark.parametrize("B,T,D,V", [(1, 1, 128, 1), (1, 7, 128, 100), (2, 15, 128, 128), (1, 60, 256, 129),
                                       (2, 33, 384, 1000), (3, 60, 128, 700), (1, 128, 128, 513), (2, 128, 256, 300),
-                                      (5, 64, 128, 257)])
+                                      (5, 64, 128, 257), (1, 64, 128, 200), (1, 65, 256, 190), (1, 129, 128, 64),
+                                      (1, 256, 128, 450)])
 def test_random_inputs_all_shapes(B, T, D, V):
     rng = np.random.default_rng(3000 + B * 1000 + T + D + V)
     h = _bf16(rng.standard_normal((B, T, D)))
@@ -74,16 +75,18 @@ def test_unsupported_width_is_rejected():
         api.lm_head_argmax(h, w, torch.ones(1, dtype=torch.int32, device="cuda"))
 
 
-def test_exact_ties_take_the_lowest_index_within_and_across_tiles():
+@pytest.mark.parametrize("T", [40, 100])     # 100 rows: the 128-row workgroups that take a tile in two passes
+def test_exact_ties_take_the_lowest_index_within_and_across_tiles(T):
     rng = np.random.default_rng(3100)
-    B, T, D, V = 1, 40, 128, 600
+    B, D, V = 1, 128, 600
     h = rng.standard_normal((B, T, D)).astype(np.float32)
     w = (rng.standard_normal((V, D)) / np.sqrt(D)).astype(np.float32)
     hb = _bf16(h)
     wb = _bf16(w)
     hf = synth.bf16_bits_to_f32(hb)
     # make row 300 a clear winner for node 0 and duplicate it at 37 (another tile), 310 (same tile, same 32-block),
-    # 350 (same tile, other block) and 599 (last tile): bit-identical logits, the lowest index must win
+    # 350 (same tile, other block; the other half of the tile) and 599 (last tile): bit-identical logits, the
+    # lowest index must win
     win = _bf16(8.0 * hf[0, 0] / float(hf[0, 0] @ hf[0, 0]))
     for v in (300, 37, 310, 350, 599):
         wb[v] = win
@@ -97,7 +100,7 @@ def test_exact_ties_take_the_lowest_index_within_and_across_tiles():
 
 def test_planted_winners_at_verify_step_size():
     rng = np.random.default_rng(3200)
-    for (B, T, D, V) in ((1, 60, 1024, 32000), (1, 60, 4096, 2048), (2, 60, 512, 4000)):
+    for (B, T, D, V) in ((1, 60, 1024, 32000), (1, 60, 4096, 2048), (2, 60, 512, 4000), (1, 128, 1024, 8000)):
         h = rng.standard_normal((B, T, D)).astype(np.float32)
         w = (rng.standard_normal((V, D)) / np.sqrt(D)).astype(np.float32)
         hb = _bf16(h)
