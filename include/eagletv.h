@@ -389,7 +389,7 @@ ETV_API int32_t etv_replicate_branches(const etv_cache_desc *h_desc, void *k_cac
  *   ETV_COMMIT_BAD_BLOCK (a needed table entry outside the pool).  A failed sequence writes nothing and keeps
  *   its dst_table row.
  *
- *  src_k, src_v in; dst_k, dst_v out   (paged: may be the same pool)
+ *  src_k, src_v in; dst_k, dst_v out   (paged: dst_k == src_k and dst_v == src_v, the one pool; else ETV_ERR_INVALID_ARG)
  *  src_table in int32 [B, max_blocks]; dst_table in/out int32 [B, max_blocks] (NULL when contiguous)
  *  path_indices in int32 [B, L_cap]; src_len, new_len in int32 [B]; kept_len, status out int32 [B]
  * All device pointers.  Requires d * elem_bytes % 16 == 0. */

@@ -346,6 +346,7 @@ extern "C" int32_t etv_commit_path_indices(const etv_cache_desc *h, const void *
     const bool paged = h->block_size > 0;
     if (paged != (src_table != nullptr) || paged != (dst_table != nullptr)) return ETV_ERR_INVALID_ARG;
     if (paged && src_table == dst_table) return ETV_ERR_INVALID_ARG;
+    if (paged && (src_k != dst_k || src_v != dst_v)) return ETV_ERR_INVALID_ARG;   // both tables index one pool
     if (!paged && (src_k == dst_k || src_v == dst_v)) return ETV_ERR_INVALID_ARG;   // a contiguous cache is rebuilt elsewhere
     if ((((uintptr_t)src_k) | ((uintptr_t)src_v) | ((uintptr_t)dst_k) | ((uintptr_t)dst_v)) & 15) return ETV_ERR_INVALID_ARG;
     hipStream_t s = etv::as_stream(stream);

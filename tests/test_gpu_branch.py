@@ -151,6 +151,15 @@ def test_path_index_commit_contiguous_and_failures():
     with pytest.raises(api.EtvError):                                      # a contiguous cache is rebuilt elsewhere
         api.commit_path_indices(ddk, ddv, ddk, ddv, to_dev(idx), to_dev(np.asarray(Ls, dtype=np.int32)),
                                 to_dev(np.asarray(Ln, dtype=np.int32)))
+    # paged: both tables index one pool, and they are two tables
+    kc, vc, src, dst = _two_tables(rng, 2, [20, 20], [20, 20], 1, "bf16", 2, 8)
+    dk_, dv_, dsrc, ddst = to_dev(kc), to_dev(vc), to_dev(src), to_dev(dst)
+    lens = to_dev(np.asarray([20, 20], dtype=np.int32))
+    ident = to_dev(np.tile(np.arange(20, dtype=np.int32), (2, 1)))
+    with pytest.raises(api.EtvError):
+        api.commit_path_indices(dk_, dv_, to_dev(kc), dv_, ident, lens, lens, src_table=dsrc, dst_table=ddst)
+    with pytest.raises(api.EtvError):
+        api.commit_path_indices(dk_, dv_, dk_, dv_, ident, lens, lens, src_table=dsrc, dst_table=dsrc)
     # paged failures: bad lengths, capacity, a hole in the destination table
     kc, vc, src, dst = _two_tables(rng, 4, [30] * 4, [30] * 4, 1, "bf16", 2, 8)
     ids = np.tile(np.arange(40, dtype=np.int32), (4, 1))
