@@ -238,3 +238,28 @@ def test_branches_through_attention_and_commit():
     torch.cuda.synchronize()
     assert np.all(rc["status"] == 0) and np.array_equal(bits_of(c["status"]), rc["status"])
     assert np.array_equal(bits_of(dk2), ck) and np.array_equal(bits_of(dv2), cv)
+
+
+def test_branch_calls_at_the_benchmark_shape():
+    """The shape bench.py times (B=8 sequences, N=4 branches, P=2040, T=60, 8 KV heads, d=128, bf16, 16-row blocks),
+    on two layers: replication, then the selected branch committed by path indices with the prefix kept and as a
+    full reorder, every byte of the pool compared with the oracle."""
+    rng = np.random.default_rng(560)
+    B, N, P, T, Hkv, d, Lyr = 8, 4, 2040, 60, 8, 128, 2
+    kc, vc, table, free = _pool(rng, B, [P + T] * B, Lyr, "bf16", Hkv, d, spare=B * N * 5 + B * 132 + 9)
+    ref, dkc, dvc, got = _replicate_case(kc, vc, table, [P] * B, [T] * B, N, free)
+    assert np.all(ref["status"] == 0) and ref["n_taken"] == B * N * ((P + T + BS - 1) // BS - P // BS)
+    okc, ovc = bits_of(dkc), bits_of(dvc)                      # the pool after replication (equal to the oracle's)
+    src = np.ascontiguousarray(ref["branch_table"][:, 1])
+    Ln = P + 6
+    idx = np.tile(np.arange(Ln, dtype=np.int32), (B, 1))
+    idx[:, P:] = P + np.asarray([0, 2, 7, 19, 33, 51], dtype=np.int32)
+    dst = np.full_like(src, -1)
+    nb = (Ln + BS - 1) // BS
+    dst[:, :nb] = free[ref["n_taken"]: ref["n_taken"] + B * nb].reshape(B, nb)
+    for fast in (True, False):
+        r = _path_case(okc, ovc, src, dst, idx, [P + T] * B, [Ln] * B, fast)
+        assert np.all(r["status"] == 0) and np.all(r["kept_len"] == (P // BS * BS if fast else 0))
+    perm = np.stack([rng.permutation(P + T)[:Ln] for _ in range(B)]).astype(np.int32)
+    r = _path_case(okc, ovc, src, dst, perm, [P + T] * B, [Ln] * B, True)   # nothing to keep: the fall-back
+    assert np.all(r["status"] == 0) and np.all(r["kept_len"] == 0)
