@@ -68,6 +68,22 @@ def test_random_inputs_all_shapes(B, T, D, V):
     _check(h, w, n)
 
 
+def test_random_row_counts_and_vocabularies_on_the_wide_path():
+    """Seeded sweep over the shapes that exercise the 128-row workgroups: last row groups of 1..127 rows, padded
+    sequences, vocabularies that end inside the first or the second half of a tile, one and several tiles."""
+    rng = np.random.default_rng(3050)
+    for case in range(14):
+        B = int(rng.integers(1, 4))
+        T = int(rng.integers(max(1, 65 // B), 140))
+        D = 128 * int(rng.integers(1, 4))
+        V = int(rng.choice([1, 33, 64, 65, 127, 128, 129, 191, 192, 193, 255, 300, 641]))
+        h = _bf16(rng.standard_normal((B, T, D)))
+        w = _bf16(rng.standard_normal((V, D)) / np.sqrt(D))
+        n = [T] + [int(rng.integers(0, T + 1)) for _ in range(B - 1)]
+        assert B * T > 64
+        _check(h, w, n)
+
+
 def test_unsupported_width_is_rejected():
     h = torch.zeros((1, 4, 64), dtype=torch.bfloat16, device="cuda")
     w = torch.zeros((10, 64), dtype=torch.bfloat16, device="cuda")
