@@ -263,3 +263,59 @@ def test_branch_calls_at_the_benchmark_shape():
     perm = np.stack([rng.permutation(P + T)[:Ln] for _ in range(B)]).astype(np.int32)
     r = _path_case(okc, ovc, src, dst, perm, [P + T] * B, [Ln] * B, True)   # nothing to keep: the fall-back
     assert np.all(r["status"] == 0) and np.all(r["kept_len"] == 0)
+
+
+def test_branch_calls_replayed_from_a_hip_graph():
+    """Replication and the commit by path indices captured once in a HIP graph and replayed with eager work in
+    between: every replay reproduces the oracle's tables and pool."""
+    rng = np.random.default_rng(570)
+    B, N, T, Hkv, d = 3, 2, 20, 2, 64
+    P = [70, 33, 16]
+    kc, vc, table, free = _pool(rng, B, [p + T for p in P], 2, "bf16", Hkv, d, spare=64)
+    okc, ovc = kc.copy(), vc.copy()
+    ref = oracle.replicate_branches(okc, ovc, table, P, [T] * B, N, free)
+    src = np.ascontiguousarray(ref["branch_table"][:, 0])
+    Ln = [p + 4 for p in P]
+    idx = np.zeros((B, max(Ln)), dtype=np.int32)
+    for b in range(B):
+        idx[b, :Ln[b]] = np.r_[np.arange(P[b]), P[b] + np.asarray([0, 3, 9, 17])]
+    dst = np.full_like(src, -1)
+    at = ref["n_taken"]
+    for b in range(B):
+        nb = (Ln[b] + BS - 1) // BS
+        dst[b, :nb] = free[at:at + nb]
+        at += nb
+    odst = dst.copy()
+    r2 = oracle.commit_path_indices(okc, ovc, okc, ovc, idx, [p + T for p in P], Ln, src_table=src, dst_table=odst,
+                                    fast=True)
+    dkc, dvc = to_dev(kc), to_dev(vc)
+    dtab, dP, dT, dfree = to_dev(table), to_dev(np.asarray(P, dtype=np.int32)), to_dev(np.full(B, T, dtype=np.int32)), to_dev(free)
+    didx, dLs, dLn = to_dev(idx), to_dev(np.asarray([p + T for p in P], dtype=np.int32)), to_dev(np.asarray(Ln, dtype=np.int32))
+    ddst = to_dev(dst)
+    res = {}
+
+    def calls():
+        res["rep"] = api.replicate_branches(dkc, dvc, dtab, dP, dT, N, dfree)
+        res["src"] = res["rep"]["branch_table"][:, 0].contiguous()
+        res["com"] = api.commit_path_indices(dkc, dvc, dkc, dvc, didx, dLs, dLn, src_table=res["src"], dst_table=ddst,
+                                             fast=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        calls()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        calls()
+    for rep in range(3):
+        dkc.copy_(to_dev(kc)); dvc.copy_(to_dev(vc)); ddst.copy_(to_dev(dst))     # eager work between the replays
+        res["rep"]["branch_table"].fill_(-9); res["com"]["kept_len"].fill_(-9)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(bits_of(res["rep"]["branch_table"]), ref["branch_table"]), rep
+        assert int(res["rep"]["n_taken"].item()) == ref["n_taken"]
+        assert np.array_equal(bits_of(res["com"]["kept_len"]), r2["kept_len"]) and np.all(bits_of(res["com"]["status"]) == 0)
+        assert np.array_equal(bits_of(ddst), odst)
+        assert np.array_equal(bits_of(dkc), okc) and np.array_equal(bits_of(dvc), ovc)
