@@ -352,10 +352,12 @@ typedef struct etv_cache_desc {
  * epilogue take branch_table viewed as [B*N, max_blocks] with the per-sequence arrays repeated N times.
  *
  *   first = prefix_len[b] / block_size, last = ceil((prefix_len[b] + tail_len[b]) / block_size),
- *   need_b = last - first (0 for a sequence with an error), block_base[b] = N * sum of need over b' < b;
- *   branch i owns free_blocks[block_base[b] + i*need_b + k] as logical block first + k.
- *   n_taken[0] = N * sum_b need_b: the caller's free list continues behind it.  If n_taken would exceed n_free,
- *   nothing is copied, n_taken[0] = 0 and every sequence that needs blocks gets ETV_BRANCH_NO_BLOCKS.
+ *   need_b = last - first (0 if the lengths are refused: ETV_COMMIT_BAD_LEN, ETV_COMMIT_CAPACITY),
+ *   block_base[b] = N * sum of need over b' < b; branch i owns free_blocks[block_base[b] + i*need_b + k] as logical
+ *   block first + k.  n_taken[0] = N * sum_b need_b: the caller's free list continues behind it.  The accounting
+ *   follows the lengths alone: a sequence refused for what a table holds (ETV_COMMIT_BAD_BLOCK, ETV_BRANCH_BAD_FREE)
+ *   keeps its share of the free list, unused.  If n_taken would exceed n_free, nothing is copied, n_taken[0] = 0
+ *   and every sequence that needs blocks gets ETV_BRANCH_NO_BLOCKS.
  *   Status bits per sequence: ETV_COMMIT_BAD_LEN (negative length), ETV_COMMIT_CAPACITY (last > max_blocks),
  *   ETV_COMMIT_BAD_BLOCK (a committed block outside the pool), ETV_BRANCH_NO_BLOCKS, ETV_BRANCH_BAD_FREE.
  *   The table rows of a failed sequence are -1 throughout; entries from `last` on are -1.

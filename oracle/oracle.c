@@ -642,12 +642,15 @@ static size_t cache_row_off(const int32_t *table_row, int block_size, int Hkv, i
  *
  * Rule (what the GPU side must reproduce exactly):
  *   first_b = P_b / bs; last_b = ceil((P_b + tail_b) / bs); need_b = last_b - first_b
- *   (0 for a sequence with an error); block_base[b] = N * sum_{b' < b} need_b';
- *   branch i of sequence b owns free_blocks[block_base[b] + i*need_b + k] as its
- *   logical block first_b + k.  n_taken = N * sum_b need_b.  If that exceeds n_free,
- *   nothing is written to the cache, n_taken = 0 and every sequence that needs
- *   blocks reports NO_BLOCKS.  Table rows of a failed sequence are all -1; entries
- *   from last_b on are -1.
+ *   (0 for a sequence whose lengths are refused: negative, or beyond the table);
+ *   block_base[b] = N * sum_{b' < b} need_b'; branch i of sequence b owns
+ *   free_blocks[block_base[b] + i*need_b + k] as its logical block first_b + k.
+ *   n_taken = N * sum_b need_b.  The accounting depends on the lengths alone: a
+ *   sequence refused for what its tables hold (a committed block or a free-list
+ *   entry outside the pool) keeps its share of the free list, unused.  If n_taken
+ *   exceeds n_free, nothing is written to the cache, n_taken = 0 and every sequence
+ *   that needs blocks reports NO_BLOCKS.  Table rows of a refused sequence are all
+ *   -1; entries from last_b on are -1.
  *   block_table [B, max_blocks]; branch_table [B, N, max_blocks]; status [B]
  * ---------------------------------------------------------------------- */
 int orc_replicate_branches(int B, int N, int Hkv, int d, int elem_bytes, int n_layers, void *k_cache, void *v_cache,
@@ -667,12 +670,12 @@ int orc_replicate_branches(int B, int N, int Hkv, int d, int elem_bytes, int n_l
         if (!st) {
             long last = (P + t + block_size - 1) / block_size;
             if (last > max_blocks) st |= ORC_COMMIT_CAPACITY;
+            if (!st) need[b] = (int)(last - P / block_size);
             if (!st)
                 for (long k = 0; k < (P + block_size - 1) / block_size; k++) {
                     int blk = block_table[(size_t)b * max_blocks + k];
                     if (blk < 0 || blk >= num_blocks) st |= ORC_COMMIT_BAD_BLOCK;
                 }
-            if (!st) need[b] = (int)(last - P / block_size);
         }
         status[b] = st;
         block_base[b] = (int32_t)total;

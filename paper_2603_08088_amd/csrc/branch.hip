@@ -10,56 +10,59 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte u
 // --------------------------------------------------------------------------------------------------------------
 // replicate_branches
 // --------------------------------------------------------------------------------------------------------------
+// Blocks a branch of one sequence owns: from the block that holds position P to the last block of the tail.  It
+// depends on the lengths alone (0 when they are refused), so every workgroup can work out any sequence's share
+// of the free list without waiting for anybody's table checks.
 struct ReplNeed {
+    int32_t st;   // ETV_COMMIT_BAD_LEN / ETV_COMMIT_CAPACITY or 0
     int first, need;
 };
-__device__ __forceinline__ ReplNeed repl_need(int P, int t, int bs, int32_t st) {
-    ReplNeed r;
-    r.first = st ? 0 : P / bs;
-    r.need = st ? 0 : (int)(((long)P + t + bs - 1) / bs) - r.first;
+__device__ __forceinline__ ReplNeed repl_need(long P, long t, int bs, int max_blocks) {
+    ReplNeed r{0, 0, 0};
+    if (P < 0 || t < 0) r.st = ETV_COMMIT_BAD_LEN;
+    else if ((P + t + bs - 1) / bs > max_blocks) r.st = ETV_COMMIT_CAPACITY;
+    if (!r.st) {
+        r.first = (int)(P / bs);
+        r.need = (int)((P + t + bs - 1) / bs) - r.first;
+    }
     return r;
 }
 
-// grid B, 256 threads: the checks of one sequence; its committed block ids are validated by all threads.
-// block_base[b] receives need_b for the scan that follows.
-__global__ void __launch_bounds__(256) replicate_check_kernel(etv_cache_desc dsc, const int32_t *__restrict__ block_table,
-                                                              const int32_t *__restrict__ prefix_len,
-                                                              const int32_t *__restrict__ tail_len,
-                                                              int32_t *__restrict__ block_base,
-                                                              int32_t *__restrict__ status) {
-    const int b = blockIdx.x;
-    const long P = prefix_len[b], t = tail_len[b];
-    const int bs = dsc.block_size;
-    int32_t st = 0;
-    if (P < 0 || t < 0) st |= ETV_COMMIT_BAD_LEN;
-    if (!st && (P + t + bs - 1) / bs > dsc.max_blocks) st |= ETV_COMMIT_CAPACITY;
-    int bad = 0;
-    if (!st) {
-        const int used = (int)((P + bs - 1) / bs);
-        for (int k = threadIdx.x; k < used; k += 256) {
-            const int blk = block_table[(size_t)b * dsc.max_blocks + k];
-            bad |= (blk < 0 || blk >= dsc.num_blocks);
-        }
+// Sum of need over the sequences [0, upto) and over all of them, by one workgroup of 256 threads.
+__device__ __forceinline__ void repl_sums(const etv_cache_desc &dsc, const int32_t *__restrict__ prefix_len,
+                                          const int32_t *__restrict__ tail_len, int upto, long &before, long &total) {
+    __shared__ long s_b[4], s_t[4];
+    long mb = 0, mt = 0;
+    for (int x = threadIdx.x; x < dsc.B; x += 256) {
+        const int nd = repl_need(prefix_len[x], tail_len[x], dsc.block_size, dsc.max_blocks).need;
+        mt += nd;
+        if (x < upto) mb += nd;
     }
-    if (__syncthreads_or(bad)) st |= ETV_COMMIT_BAD_BLOCK;
-    if (threadIdx.x == 0) {
-        status[b] = st;
-        block_base[b] = repl_need((int)P, (int)t, bs, st).need;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        mb += __shfl_xor(mb, off);
+        mt += __shfl_xor(mt, off);
     }
+    if ((threadIdx.x & 63) == 0) { s_b[threadIdx.x >> 6] = mb; s_t[threadIdx.x >> 6] = mt; }
+    __syncthreads();
+    before = s_b[0] + s_b[1] + s_b[2] + s_b[3];
+    total = s_t[0] + s_t[1] + s_t[2] + s_t[3];
 }
 
-// one workgroup of 256 threads: block_base[b] = N * (sum of need over the sequences before b), the total, and the
-// all-or-nothing decision against the length of the free list.
-__global__ void __launch_bounds__(256) replicate_scan_kernel(int B, int N, int n_free, int32_t *__restrict__ block_base,
-                                                             int32_t *__restrict__ n_taken, int32_t *__restrict__ status) {
+// Large batches: one workgroup writes block_base[] and n_taken ahead of the fill kernel, which then reads them
+// instead of summing over the batch itself.  Exclusive scan in chunks of 256 sequences with a running carry.
+__global__ void __launch_bounds__(256) replicate_scan_kernel(etv_cache_desc dsc, const int32_t *__restrict__ prefix_len,
+                                                             const int32_t *__restrict__ tail_len, int N, int n_free,
+                                                             int32_t *__restrict__ block_base,
+                                                             int32_t *__restrict__ n_taken) {
     __shared__ int s_part[256];
-    __shared__ int s_carry;
+    __shared__ long s_carry;
     const int t = threadIdx.x;
     if (t == 0) s_carry = 0;
     __syncthreads();
-    for (int b0 = 0; b0 < B; b0 += 256) {
+    for (int b0 = 0; b0 < dsc.B; b0 += 256) {
         const int b = b0 + t;
-        const int mine = b < B ? block_base[b] : 0;
+        const int mine = b < dsc.B ? repl_need(prefix_len[b], tail_len[b], dsc.block_size, dsc.max_blocks).need : 0;
         s_part[t] = mine;
         __syncthreads();
         for (int off = 1; off < 256; off <<= 1) {   // inclusive scan of the 256 entries
@@ -68,62 +71,87 @@ __global__ void __launch_bounds__(256) replicate_scan_kernel(int B, int N, int n
             s_part[t] += add;
             __syncthreads();
         }
-        const int carry = s_carry;
-        if (b < B) block_base[b] = N * (carry + s_part[t] - mine);
+        const long carry = s_carry;
+        if (b < dsc.B) block_base[b] = (int32_t)(N * (carry + s_part[t] - mine));
         __syncthreads();
         if (t == 255) s_carry = carry + s_part[255];
         __syncthreads();
     }
-    const long total = (long)N * s_carry;
-    const bool fits = total <= n_free;
-    if (t == 0) n_taken[0] = fits ? (int32_t)total : 0;
-    if (!fits)
-        for (int b = t; b < B; b += 256) {
-            // a sequence with need > 0 is one whose successor's base moved on; the last one compares with the total
-            const long next = b + 1 < B ? block_base[b + 1] : total;
-            if (next > block_base[b]) status[b] |= ETV_BRANCH_NO_BLOCKS;
-        }
+    if (t == 0) {
+        const long total = (long)N * s_carry;
+        n_taken[0] = total <= n_free ? (int32_t)total : 0;   // 0 with sequences that need blocks: it did not fit
+    }
 }
 
-// grid (N, B, n_layers), 256 threads: branch i of sequence b.  Layer 0's workgroup writes the table row; every
-// layer's workgroup copies the committed rows of the partly filled block into the branch's own block.
+// grid (N, B, n_layers), 256 threads: branch i of sequence b in layer l.  Every workgroup derives the sequence's
+// share of the free list (PRESCANNED: reads it), checks the sequence's tables, and copies the committed rows of
+// the partly filled block into the branch's own block for its layer; layer 0's workgroup also writes the table
+// row, and the first branch's the per-sequence outputs.
+template <bool PRESCANNED>
 __global__ void __launch_bounds__(256) replicate_fill_kernel(etv_cache_desc dsc, uint8_t *__restrict__ k_cache,
                                                              uint8_t *__restrict__ v_cache,
                                                              const int32_t *__restrict__ block_table,
                                                              const int32_t *__restrict__ prefix_len,
                                                              const int32_t *__restrict__ tail_len, int N,
-                                                             const int32_t *__restrict__ free_blocks,
-                                                             const int32_t *__restrict__ block_base,
+                                                             const int32_t *__restrict__ free_blocks, int n_free,
+                                                             int32_t *__restrict__ block_base,
                                                              int32_t *__restrict__ branch_table,
+                                                             int32_t *__restrict__ n_taken,
                                                              int32_t *__restrict__ status) {
     const int i = blockIdx.x, b = blockIdx.y, l = blockIdx.z, t = threadIdx.x;
     const int bs = dsc.block_size;
-    const int32_t st = status[b] & ~ETV_BRANCH_BAD_FREE;   // that bit is this kernel's own, set below
     const int P = prefix_len[b];
-    const ReplNeed rn = repl_need(P, tail_len[b], bs, st);
-    const int base = block_base[b];
-    int bad = 0;
-    for (int x = t; x < N * rn.need; x += 256) {
-        const int blk = free_blocks[base + x];
-        bad |= (blk < 0 || blk >= dsc.num_blocks);
+    const ReplNeed rn = repl_need(P, tail_len[b], bs, dsc.max_blocks);
+    long base;
+    bool fits;
+    if (PRESCANNED) {
+        base = block_base[b];
+        fits = n_taken[0] > 0 || rn.need == 0;   // the scan kernel wrote 0 if the demand exceeds the free list
+    } else {
+        long before, total;
+        repl_sums(dsc, prefix_len, tail_len, b, before, total);
+        base = (long)N * before;
+        total *= N;
+        fits = total <= n_free;
+        if (i == 0 && b == 0 && l == 0 && t == 0) n_taken[0] = fits ? (int32_t)total : 0;
     }
-    // looked up ahead of the barrier so that the copy below does not start with another trip to memory
-    const int rows = st ? 0 : P - rn.first * bs;   // committed rows inside the partly filled block
-    const int src_blk = rows > 0 ? block_table[(size_t)b * dsc.max_blocks + rn.first] : 0;
-    const int dst_blk = rows > 0 ? free_blocks[base + (size_t)i * rn.need] : 0;
-    const bool bad_free = __syncthreads_or(bad) != 0;
-    const bool failed = st != 0 || bad_free;
+    int32_t st = rn.st;
+    if (!fits && rn.need > 0) st |= ETV_BRANCH_NO_BLOCKS;
+    // Table checks, all loads in one go and one barrier: the committed blocks, and the sequence's share of the
+    // free list (which counts only for a sequence that is good so far).  The blocks of the partial-block copy are
+    // looked up here too, so that the copy does not start with another trip to memory.
+    int bad = 0;
+    if (!rn.st)
+        for (int k = t; k < (P + bs - 1) / bs; k += 256) {
+            const int blk = block_table[(size_t)b * dsc.max_blocks + k];
+            bad |= (blk < 0 || blk >= dsc.num_blocks) ? 1 : 0;
+        }
+    if (!st)
+        for (int x = t; x < N * rn.need; x += 256) {
+            const int blk = free_blocks[base + x];
+            bad |= (blk < 0 || blk >= dsc.num_blocks) ? 2 : 0;
+        }
+    const int rows0 = st ? 0 : P - rn.first * bs;   // committed rows inside the partly filled block
+    const int src_blk = rows0 > 0 ? block_table[(size_t)b * dsc.max_blocks + rn.first] : 0;
+    const int dst_blk = rows0 > 0 ? free_blocks[base + (size_t)i * rn.need] : 0;
+    const int any_block = __syncthreads_or(bad & 1), any_free = __syncthreads_or(bad & 2);   // every load is out by now
+    if (any_block) st |= ETV_COMMIT_BAD_BLOCK;
+    else if (any_free) st |= ETV_BRANCH_BAD_FREE;
+    const int rows = st ? 0 : rows0;
     const int32_t *mine = free_blocks + base + (size_t)i * rn.need;
     if (l == 0) {
-        if (i == 0 && t == 0 && bad_free) status[b] = st | ETV_BRANCH_BAD_FREE;
+        if (i == 0 && t == 0) {
+            status[b] = st;
+            if (!PRESCANNED) block_base[b] = (int32_t)base;
+        }
         int32_t *row = branch_table + ((size_t)b * N + i) * dsc.max_blocks;
         for (int k = t; k < dsc.max_blocks; k += 256) {
             int32_t v = -1;
-            if (!failed && k < rn.first + rn.need) v = k < rn.first ? block_table[(size_t)b * dsc.max_blocks + k] : mine[k - rn.first];
+            if (!st && k < rn.first + rn.need) v = k < rn.first ? block_table[(size_t)b * dsc.max_blocks + k] : mine[k - rn.first];
             row[k] = v;
         }
     }
-    if (failed || rows <= 0) return;
+    if (st || rows <= 0) return;
     const size_t head_bytes = (size_t)dsc.d * dsc.elem_bytes;
     const int upr = (int)(head_bytes / 16);              // 16-byte units per row of one head
     const int per_head = rows * upr;                     // the rows of a head are consecutive memory
@@ -317,18 +345,21 @@ extern "C" int32_t etv_replicate_branches(const etv_cache_desc *h, void *k_cache
     if ((((uintptr_t)k_cache) | ((uintptr_t)v_cache)) & 15) return ETV_ERR_INVALID_ARG;
     if ((long)h->B * N * h->max_blocks > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;   // block_base is an int32
     hipStream_t s = etv::as_stream(stream);
-    if (h->B > 0) {
-        hipLaunchKernelGGL(etv::replicate_check_kernel, dim3(h->B), dim3(256), 0, s, *h, block_table, prefix_len,
-                           tail_len, block_base, status);
-        rc = etv::check_launch();
-        if (rc != ETV_OK) return rc;
+    uint8_t *kc = static_cast<uint8_t *>(k_cache), *vc = static_cast<uint8_t *>(v_cache);
+    const dim3 grid(N, h->B, h->n_layers);
+    if (h->B > 0 && h->B <= 256) {
+        // every workgroup sums the batch's block demand itself: one launch
+        hipLaunchKernelGGL(etv::replicate_fill_kernel<false>, grid, dim3(256), 0, s, *h, kc, vc, block_table, prefix_len,
+                           tail_len, N, free_blocks, n_free, block_base, branch_table, n_taken, status);
+        return etv::check_launch();
     }
-    hipLaunchKernelGGL(etv::replicate_scan_kernel, dim3(1), dim3(256), 0, s, h->B, N, n_free, block_base, n_taken, status);
+    // large batches (and the empty one, which only needs n_taken = 0): a one-workgroup scan first
+    hipLaunchKernelGGL(etv::replicate_scan_kernel, dim3(1), dim3(256), 0, s, *h, prefix_len, tail_len, N, n_free,
+                       block_base, n_taken);
     rc = etv::check_launch();
     if (rc != ETV_OK || h->B == 0) return rc;
-    hipLaunchKernelGGL(etv::replicate_fill_kernel, dim3(N, h->B, h->n_layers), dim3(256), 0, s, *h,
-                       static_cast<uint8_t *>(k_cache), static_cast<uint8_t *>(v_cache), block_table, prefix_len,
-                       tail_len, N, free_blocks, block_base, branch_table, status);
+    hipLaunchKernelGGL(etv::replicate_fill_kernel<true>, grid, dim3(256), 0, s, *h, kc, vc, block_table, prefix_len,
+                       tail_len, N, free_blocks, n_free, block_base, branch_table, n_taken, status);
     return etv::check_launch();
 }
 

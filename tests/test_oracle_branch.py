@@ -104,7 +104,13 @@ def test_replication_failures_take_nothing():
     assert r["status"].tolist() == [0, oracle.COMMIT_CAPACITY, 0]
     r = oracle.replicate_branches(kc, vc, bad, [20, 30, -1], [10, 10, 10], 2, free)
     assert r["status"].tolist() == [0, oracle.COMMIT_BAD_BLOCK, oracle.COMMIT_BAD_LEN]
-    assert r["n_taken"] == 2 and np.all(r["branch_table"][1:] == -1)
+    # the accounting follows the lengths alone: the sequence refused for its table keeps its share (2 x 2 blocks),
+    # the one refused for its length has none
+    assert r["n_taken"] == 2 + 4 and r["block_base"].tolist() == [0, 2, 6] and np.all(r["branch_table"][1:] == -1)
+    good = oracle.replicate_branches(kc.copy(), vc.copy(), table, [20, 30, 40], [10, 10, 10], 2, free)
+    worse = oracle.replicate_branches(kc.copy(), vc.copy(), bad, [20, 30, 40], [10, 10, 10], 2, free)
+    assert np.array_equal(good["block_base"], worse["block_base"]) and good["n_taken"] == worse["n_taken"]
+    assert np.array_equal(good["branch_table"][[0, 2]], worse["branch_table"][[0, 2]])
     f2 = free.copy()
     f2[1] = -3
     r = oracle.replicate_branches(kc.copy(), vc, table, [20, 30, 40], [10, 10, 10], 2, f2)
