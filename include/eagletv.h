@@ -181,6 +181,24 @@ ETV_API int32_t etv_tree_verify_attention(const etv_attn_desc *h_desc, const voi
                                   const void *kt, const void *vt, const uint64_t *bitmask, const int32_t *n_nodes,
                                   void *out, float *lse, void *workspace, size_t workspace_bytes, void *stream);
 
+/* etv_tree_verify_attention for callers that cannot allocate device memory or carry a workspace around: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * errors, without workspace / workspace_bytes: the partial results of the key splits go to a fixed array of
+ * ETV_ATTN_STATIC_WORKSPACE_BYTES bytes of device memory inside the library (every GPU the library runs on holds
+ * its own copy until the process ends).  The call allocates and frees nothing.
+ *  - A shape whose etv_tree_verify_attention_workspace_bytes() exceeds the array returns
+ *    ETV_ERR_WORKSPACE_TOO_SMALL and launches nothing (use the call above with a workspace of your own, or a
+ *    larger h_desc->kv_split, which means fewer splits).
+ *  - All calls on one GPU share that GPU's array: two of them must not overlap in time (different streams without
+ *    an ordering between them, or different host threads, race); calls on one stream are ordered and safe.
+ *  - The device that is current when the call is made must be the one `stream` and the buffers belong to. */
+#define ETV_ATTN_STATIC_WORKSPACE_BYTES (64u << 20)
+
+ETV_API int32_t etv_tree_verify_attention_static(const etv_attn_desc *h_desc, const void *q, const void *k_cache,
+                                         const void *v_cache, const int32_t *block_table, const int32_t *prefix_len,
+                                         const void *kt, const void *vt, const uint64_t *bitmask,
+                                         const int32_t *n_nodes, void *out, float *lse, void *stream);
+
 /* ---------------------------------------------------------------------------
  * safe_gather_paths - contribution 2, Section 3.2 "Dummy-root indexing" and
  * "Padding and batch semantics", Section 2.5 (device-defined for every index value).

@@ -28,10 +28,12 @@ ATTN_FLAG_SMALL_WG = 2
 ATTN_FLAG_WHOLE_TILE = 4
 ATTN_FLAG_KEY_HALVES = 8
 MAX_TREE, ATTN_MAX_TREE = 256, 256
+ATTN_STATIC_WORKSPACE_BYTES = 64 << 20
 
 EXPORTS = ("etv_status_string", "etv_version", "etv_last_hip_error", "etv_hbm_read_probe", "etv_build_tree_mask",
            "etv_tensorize_tree",
-           "etv_tree_verify_attention_workspace_bytes", "etv_tree_verify_attention", "etv_safe_gather_paths",
+           "etv_tree_verify_attention_workspace_bytes", "etv_tree_verify_attention",
+           "etv_tree_verify_attention_static", "etv_safe_gather_paths",
            "etv_evaluate_posterior_workspace_bytes", "etv_evaluate_posterior", "etv_commit_accepted_kv",
            "etv_verify_epilogue", "etv_lm_head_argmax_workspace_bytes", "etv_lm_head_argmax",
            "etv_lm_head_packed_bytes", "etv_pack_lm_head", "etv_replicate_branches", "etv_commit_path_indices")
@@ -84,6 +86,8 @@ def lib():
         l.etv_tree_verify_attention_workspace_bytes.argtypes = [C.POINTER(AttnDesc)]
         l.etv_tree_verify_attention.restype = i32
         l.etv_tree_verify_attention.argtypes = [C.POINTER(AttnDesc)] + [vp] * 12 + [sz, vp]
+        l.etv_tree_verify_attention_static.restype = i32
+        l.etv_tree_verify_attention_static.argtypes = [C.POINTER(AttnDesc)] + [vp] * 12
         l.etv_safe_gather_paths.restype = i32
         l.etv_safe_gather_paths.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, sz, vp, vp, vp, vp]
         l.etv_lm_head_argmax_workspace_bytes.restype = sz
@@ -227,6 +231,19 @@ def tree_verify_attention(q, k_cache, v_cache, prefix_len, kt, vt, bitmask, n_no
                                          _ptr(prefix_len), _ptr(kt), _ptr(vt), _ptr(bitmask), _ptr(n_nodes),
                                          _ptr(out), _ptr(lse), _ptr(workspace), workspace.numel(), _stream())
     _check("etv_tree_verify_attention", rc)
+    return out, lse
+
+
+def tree_verify_attention_static(q, k_cache, v_cache, prefix_len, kt, vt, bitmask, n_nodes, out, lse=None, *,
+                                 P_max: int, block_table=None, scale: float = 0.0, kv_split: int = 0, flags: int = 0,
+                                 desc: Optional[AttnDesc] = None):
+    """tree_verify_attention with the split partials in the library's own fixed device array: the caller passes
+    every input and output (`out`, optionally `lse`) and nothing is allocated, here or in the library."""
+    dsc = desc or attn_desc(q, kt, k_cache, block_table, P_max, scale, kv_split, flags)
+    rc = lib().etv_tree_verify_attention_static(C.byref(dsc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                                _ptr(block_table), _ptr(prefix_len), _ptr(kt), _ptr(vt),
+                                                _ptr(bitmask), _ptr(n_nodes), _ptr(out), _ptr(lse), _stream())
+    _check("etv_tree_verify_attention_static", rc)
     return out, lse
 
 

@@ -12,6 +12,7 @@
 //
 // Scores are kept in "scaled log2 units" t = (q.k) * scale * log2(e) so that exp is a bare v_exp_f32.
 #include "etv_common.h"
+#include <atomic>
 
 namespace etv {
 
@@ -1082,12 +1083,12 @@ extern "C" size_t etv_tree_verify_attention_workspace_bytes(const etv_attn_desc 
     return rows * ((size_t)h->d + 2) * sizeof(float) + 512;
 }
 
-extern "C" int32_t etv_tree_verify_attention(const etv_attn_desc *h, const void *q, const void *k_cache,
-                                             const void *v_cache, const int32_t *block_table,
-                                             const int32_t *prefix_len, const void *kt, const void *vt,
-                                             const uint64_t *bitmask, const int32_t *n_nodes, void *out, float *lse,
-                                             void *workspace, size_t workspace_bytes, void *stream) {
-    using namespace etv;
+namespace etv {
+// argument checks and launches shared by the two entry points (caller's workspace / the library's static one)
+static int32_t attention_run(const etv_attn_desc *h, const void *q, const void *k_cache, const void *v_cache,
+                             const int32_t *block_table, const int32_t *prefix_len, const void *kt, const void *vt,
+                             const uint64_t *bitmask, const int32_t *n_nodes, void *out, float *lse, void *workspace,
+                             size_t workspace_bytes, void *stream) {
     if (!h || !q || !prefix_len || !bitmask || !n_nodes || !out) return ETV_ERR_INVALID_ARG;
     if ((kt == nullptr) != (vt == nullptr)) return ETV_ERR_INVALID_ARG;
     const bool tail = (kt == nullptr);  // in-place branch cache: the tree rows are in the cache behind the prefix
@@ -1183,4 +1184,71 @@ extern "C" int32_t etv_tree_verify_attention(const etv_attn_desc *h, const void 
     else
         hipLaunchKernelGGL((attn_combine_kernel<uint16_t, 128, 1>), cgrid, dim3(256), 0, st, p);
     return check_launch();
+}
+}  // namespace etv
+
+extern "C" int32_t etv_tree_verify_attention(const etv_attn_desc *h, const void *q, const void *k_cache,
+                                             const void *v_cache, const int32_t *block_table,
+                                             const int32_t *prefix_len, const void *kt, const void *vt,
+                                             const uint64_t *bitmask, const int32_t *n_nodes, void *out, float *lse,
+                                             void *workspace, size_t workspace_bytes, void *stream) {
+    return etv::attention_run(h, q, k_cache, v_cache, block_table, prefix_len, kt, vt, bitmask, n_nodes, out, lse,
+                              workspace, workspace_bytes, stream);
+}
+
+// ----------------------------------------------------------------------------------------------
+// The same call for callers that cannot allocate or carry a workspace (code under graph capture, serving loops):
+// the split partials go to a fixed array in device memory that the library owns.  Each GPU holds its own copy
+// of the array at its own address; the address is asked for once per device and only that pointer is ever
+// handed to a kernel (the array's name is a host-side stand-in in host code, not a device address).
+// ----------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[ETV_ATTN_STATIC_WORKSPACE_BYTES];
+
+namespace etv {
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];           // per device, filled on the first call on that device
+static std::atomic<int> g_scratch_state[kMaxDevices];  // 0 unset, 1 being set, 2 set
+
+static int32_t static_scratch(void **ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ETV_ERR_HIP;
+    if (g_scratch_state[dev].load(std::memory_order_acquire) != 2) {
+        int expect = 0;
+        if (g_scratch_state[dev].compare_exchange_strong(expect, 1, std::memory_order_acq_rel)) {
+            void *d = nullptr;
+            const hipError_t e = hipGetSymbolAddress(&d, HIP_SYMBOL(scratch));  // device `dev` is current
+            if (e != hipSuccess || d == nullptr) {
+                g_last_hip_error = (int32_t)e;
+                g_scratch_state[dev].store(0, std::memory_order_release);
+                return ETV_ERR_HIP;
+            }
+            g_scratch_ptr[dev] = d;
+            g_scratch_state[dev].store(2, std::memory_order_release);
+        } else {
+            while (g_scratch_state[dev].load(std::memory_order_acquire) == 1) { /* another thread is asking */ }
+            if (g_scratch_state[dev].load(std::memory_order_acquire) != 2) return ETV_ERR_HIP;
+        }
+    }
+    *ptr = g_scratch_ptr[dev];
+    return ETV_OK;
+}
+}  // namespace etv
+
+extern "C" int32_t etv_tree_verify_attention_static(const etv_attn_desc *h, const void *q, const void *k_cache,
+                                                    const void *v_cache, const int32_t *block_table,
+                                                    const int32_t *prefix_len, const void *kt, const void *vt,
+                                                    const uint64_t *bitmask, const int32_t *n_nodes, void *out,
+                                                    float *lse, void *stream) {
+    if (!h) return ETV_ERR_INVALID_ARG;
+    // sizes beyond the array are refused before anything is launched
+    if (etv_tree_verify_attention_workspace_bytes(h) > (size_t)ETV_ATTN_STATIC_WORKSPACE_BYTES)
+        return ETV_ERR_WORKSPACE_TOO_SMALL;
+    void *ws = nullptr;
+    const int32_t rc = etv::static_scratch(&ws);
+    if (rc != ETV_OK) return rc;
+    // Nothing in the array has to start at zero: a launch writes every (m, l, O) partial it later merges, and
+    // never reads one it has not written (absent splits and padded rows are skipped), so the last call's
+    // contents are harmless.
+    return etv::attention_run(h, q, k_cache, v_cache, block_table, prefix_len, kt, vt, bitmask, n_nodes, out, lse, ws,
+                              (size_t)ETV_ATTN_STATIC_WORKSPACE_BYTES, stream);
 }
