@@ -8,8 +8,17 @@ with every input already resident in HBM.  The step is captured once into a HIP 
 set and replayed; cache sets are rotated so that consecutive steps stream K/V from HBM, not from
 the 256 MB memory-side cache.  Prints ONE JSON line (metric: tree-verify tokens/s).
 
+The default workload is the largest single-GPU configuration: the T = 128, depth 10 cell of the budget sweep
+(B = 32 sequences, 4096-token paged prefixes, 32 layers).  Beside the headline the line carries
+  * `roofline`: the attention launch (the dominant kernel) against the published peaks and against what this
+    machine sustains in the same run (a streaming-read probe and a register-only MFMA probe);
+  * `timing`: median and minimum over >= 50 event-timed replays of the whole step and of each part of it;
+  * `configs`: the attention launch at every configuration (C2, C3, C4 and the T = 8 ... 128 sweep cells), median and
+    minimum over >= 50 timed samples, with both roofline fractions;
+  * `cpu_baseline`: the CPU oracle timed on a bounded sample of the same workload and scaled to a step.
+
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c2_paged|c3|c4|c5_T<T>_D<D>[_B<B>_P<P>]] [--layers L]
-                  [--no-graph] [--skip-cpu] [--kv-split N]
+                  [--no-graph] [--skip-cpu] [--no-configs] [--kv-split N]
 """
 from __future__ import annotations
 
@@ -30,9 +39,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c5_T128_D10")
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
@@ -43,26 +52,34 @@ def parse_args():
                     help="skip the timing of branch replication and the commit by path indices")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one device copy of this many MiB (a known-size kernel to calibrate profiler byte counters)")
+    ap.add_argument("--no-configs", action="store_true", help="skip the per-configuration table of attention launches")
+    ap.add_argument("--samples", type=int, default=50, help="event-timed samples per figure (at least 50)")
+    ap.add_argument("--no-probes", action="store_true", help="skip the stream-read and MFMA probes")
     ap.add_argument("--sets", type=int, default=0, help="cache sets to rotate over (0 = enough to exceed 640 MB)")
     return ap.parse_args()
 
 
-def make_host_workload(name):
+def make_host_workload(name, with_cache=False, with_logits=True):
     from paper_2603_08088_amd import synth
+    kw = dict(with_cache=with_cache, with_logits=with_logits)
     if name == "c2":
-        return synth.config2(with_cache=False), "7B-class GQA verify step: B=1, 32/8 heads, d=128, bf16, P=2048, 60-node tree"
+        return synth.config2(**kw), "7B-class GQA verify step: B=1, 32/8 heads, d=128, bf16, P=2048, 60-node tree"
     if name == "c2_paged":
-        return synth.config2(paged=True, with_cache=False), "config 2 with a paged prefix cache"
+        return synth.config2(paged=True, **kw), "config 2 with a paged prefix cache"
     if name == "c3":
-        return synth.config3(with_cache=False), "ragged batch: B=8, P~U[512,8192], paged, 60-node trees"
+        return synth.config3(**kw), "ragged batch: B=8, P~U[512,8192], paged, 60-node trees"
     if name == "c4":
-        return synth.config4(with_cache=False), "long context: B=1, P=32768, 128-node tree"
+        return synth.config4(**kw), "long context: B=1, P=32768, 128-node tree"
     m = re.fullmatch(r"c5_T(\d+)_D(\d+)(?:_B(\d+)_P(\d+))?", name)
     if m:
         B, P = int(m.group(3) or 32), int(m.group(4) or 4096)
-        return synth.config5(int(m.group(1)), int(m.group(2)), B=B, P=P, with_cache=False), \
-            f"budget sweep cell: B={B}, P={P} paged, T={m.group(1)}, depth {m.group(2)}"
+        return synth.config5(int(m.group(1)), int(m.group(2)), B=B, P=P, **kw), \
+            f"budget sweep cell: B={B}, P={P} paged, T={m.group(1)}, depth {m.group(2)}, 32/8 heads, d=128, bf16"
     raise SystemExit(f"unknown workload {name}")
+
+
+# the attention launch of every configuration (the sweep cells at the depth whose traffic counters are on file)
+TABLE_CONFIGS = ("c2", "c3", "c4", "c5_T8_D4", "c5_T16_D10", "c5_T32_D6", "c5_T64_D8", "c5_T128_D10")
 
 
 class Step:
@@ -72,8 +89,7 @@ class Step:
         import numpy as np
         import torch
         from paper_2603_08088_amd import api
-        sys.path.insert(0, os.path.join(ROOT, "tests"))
-        from gpu_helpers import to_dev
+        from paper_2603_08088_amd.devio import to_dev
         self.api, self.torch, self.wl, self.L = api, torch, wl, layers
         dev = "cuda:0"
         gen = torch.Generator(device=dev)
@@ -145,25 +161,19 @@ class Step:
         api = self.api
         api.tensorize_tree(self.parent, self.n_nodes, self.prefix_len, self.L_max, self.W, out=self.mask_out)
         self.attention_layers(s)
-        # gather + acceptance + commit as the fused epilogue (three launches); the new prefix length goes to its
-        # own buffer so that every timed step sees the same prefix
+        self.epilogue(s)
+
+    def epilogue(self, s):
+        # gather + acceptance + commit as the fused epilogue; the new prefix length goes to its own buffer so that
+        # every timed step sees the same prefix
+        api = self.api
         api.verify_epilogue(self.logits, self.tokens, self.retrieve, self.n_nodes, self.kt, self.vt, self.kc[s],
                             self.vc[s], self.prefix_len, self.capacity, block_table=self.block_table, dummy=0,
                             src=self.tokens3, workspace=self.post_ws, gather_out=self.gather_out,
                             post_out=self.post_out, commit_out=self.commit_out)
 
     def capture(self, fn):
-        torch = self.torch
-        g = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            fn()                      # warm up outside capture
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        with torch.cuda.graph(g):
-            fn()
-        return g
+        return capture(self.torch, fn)
 
 
 def attention_algorithmic(wl):
@@ -178,39 +188,198 @@ def attention_algorithmic(wl):
     return by, fl
 
 
-def cpu_baseline(wl_name, layers):
-    """The oracle as it stands, timed on the host cores over one whole step of the same workload shape
-    (the layer loop re-runs the oracle attention on one layer's host data: time does not depend on values)."""
+def event_samples(torch, fn, n, warm=5):
+    """Milliseconds of n calls of fn, each between its own pair of HIP events on the launch stream."""
+    for i in range(warm):
+        fn(i)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    ev[0].record()
+    for i in range(n):
+        fn(warm + i)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    return [ev[i].elapsed_time(ev[i + 1]) for i in range(n)]
+
+
+def stats_us(samples_ms, per=1):
+    import statistics
+    us = [x * 1e3 / per for x in samples_ms]
+    return {"median_us": statistics.median(us), "min_us": min(us), "mean_us": sum(us) / len(us), "samples": len(us)}
+
+
+def traffic_on_file(name):
+    """HBM bytes per attention launch from the rocprofv3 counter runs kept under profiles/ (None if not taken)."""
+    tpath = os.path.join(ROOT, "profiles", f"attention_hbm_traffic_{name}.txt")
+    if os.path.exists(tpath):
+        return json.load(open(tpath)).get("hbm_bytes_per_launch")
+    return None
+
+
+def fractions(by, fl, us, peaks):
+    """Both roofline fractions of a launch of `us` microseconds, against the published and the measured ceilings."""
+    gbs, tfl = by / (us * 1e-6) / 1e9, fl / (us * 1e-6) / 1e12
+    out = {"hbm_gbs": gbs, "mfma_tflops": tfl, "hbm_frac": gbs / HBM_PEAK_GBS, "mfma_frac": tfl / MFMA_BF16_PEAK_TFLOPS,
+           "bound": "hbm" if by / HBM_PEAK_GBS / 1e9 >= fl / MFMA_BF16_PEAK_TFLOPS / 1e12 else "mfma"}
+    if peaks.get("stream_gbs"):
+        out["hbm_frac_of_measured"] = gbs / peaks["stream_gbs"]
+    if peaks.get("mfma_sustained_tflops"):
+        out["mfma_frac_of_measured"] = tfl / peaks["mfma_sustained_tflops"]
+    return out
+
+
+def run_probes(torch):
+    """What this machine sustains, measured in the same run: a 1 GiB streaming read, and a register-only MFMA loop
+    on every compute unit, first launch and sustained (the chip lowers its clock under matrix load)."""
+    from paper_2603_08088_amd import probe
+    buf = torch.empty(2 ** 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
+    ms = event_samples(torch, lambda i: probe.hbm_read_probe(buf, sink), 10, warm=2)
+    stream_gbs = buf.numel() / (min(ms) * 1e-3) / 1e9
+    stream_gbs_median = buf.numel() / (sorted(ms)[len(ms) // 2] * 1e-3) / 1e9
+    del buf
+    torch.cuda.synchronize()
+    time.sleep(0.5)                       # let the clocks recover so that the first launch is a cold one
+    iters = 128                           # ~0.55 TFLOP per launch: a few hundred microseconds, like an attention launch
+    fl = probe.mfma_bf16_probe_flops(iters)
+    ms = event_samples(torch, lambda i: probe.mfma_bf16_probe(iters, sink), 200, warm=0)
+    tail = sorted(ms[100:])
+    return {"stream_gbs": stream_gbs, "stream_gbs_median": stream_gbs_median,
+            "mfma_first_launch_tflops": fl / (ms[0] * 1e-3) / 1e12,
+            "mfma_best_launch_tflops": fl / (min(ms) * 1e-3) / 1e12,
+            "mfma_sustained_tflops": fl / (tail[len(tail) // 2] * 1e-3) / 1e12,
+            "mfma_probe": f"200 back-to-back launches of {fl / 1e12:.2f} TFLOP (v_mfma_f32_32x32x16_bf16 from registers, "
+                          "2048 workgroups x 4 wavefronts); sustained = median of launches 101-200"}
+
+
+class AttnOnly:
+    """Attention launches of one configuration over enough layers of cache that K/V streams from HBM."""
+
+    def __init__(self, name, torch, api):
+        from paper_2603_08088_amd.devio import to_dev
+        wl, self.text = make_host_workload(name, with_logits=False)
+        self.wl, self.api, self.torch = wl, api, torch
+        dev, bf = "cuda:0", torch.bfloat16
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(26030808)
+        B, T, Hq, Hkv, d = wl.B, wl.T_max, wl.Hq, wl.Hkv, wl.d
+        cshape = (wl.num_blocks, Hkv, 16, d) if wl.paged else (B, wl.P_cap, Hkv, d)
+        per_layer = 2 * 2
+        for x in cshape:
+            per_layer *= x
+        self.layers = max(2, -(-640 * 2 ** 20 // per_layer))
+        L = self.layers
+        self.q = torch.randn((L, B, T, Hq, d), generator=gen, device=dev).to(bf)
+        self.kt = torch.randn((L, B, T, Hkv, d), generator=gen, device=dev).to(bf)
+        self.vt = torch.randn((L, B, T, Hkv, d), generator=gen, device=dev).to(bf)
+        self.kc = torch.empty((L,) + cshape, dtype=bf, device=dev)
+        self.vc = torch.empty((L,) + cshape, dtype=bf, device=dev)
+        for l in range(L):
+            self.kc[l].copy_(torch.randn(cshape, generator=gen, device=dev))
+            self.vc[l].copy_(torch.randn(cshape, generator=gen, device=dev))
+        self.out = torch.empty_like(self.q)
+        self.parent, self.n_nodes = to_dev(wl.parent), to_dev(wl.n_nodes)
+        self.prefix_len, self.block_table = to_dev(wl.prefix_len), to_dev(wl.block_table)
+        self.P_max = int(wl.prefix_len.max())
+        self.bitmask = api.build_tree_mask(self.parent, self.n_nodes, want_dense=False, want_depth=False)["bitmask"]
+        self.desc = api.attn_desc(self.q[0], self.kt[0], self.kc[0], self.block_table, self.P_max)
+        self.ws = torch.empty((max(256, api.tree_verify_attention_workspace_bytes(self.desc)),), dtype=torch.uint8,
+                              device=dev)
+
+    def launches(self):
+        for l in range(self.layers):
+            self.api.tree_verify_attention(self.q[l], self.kc[l], self.vc[l], self.prefix_len, self.kt[l], self.vt[l],
+                                           self.bitmask, self.n_nodes, P_max=self.P_max, block_table=self.block_table,
+                                           out=self.out[l], want_lse=False, workspace=self.ws, desc=self.desc)
+
+
+def capture(torch, fn):
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()                      # warm up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g):
+        fn()
+    return g
+
+
+def configs_table(torch, api, n_samples, peaks, headline=None):
+    """The attention launch at every configuration: a sample is one replay of a graph of `layers` launches over
+    distinct layer caches (so K/V comes from HBM); median and minimum over the samples, per launch."""
+    rows = {}
+    for name in TABLE_CONFIGS:
+        if headline is not None and name == headline[0]:
+            rows[name] = headline[1]
+            continue
+        a = AttnOnly(name, torch, api)
+        g = capture(torch, a.launches)
+        ms = event_samples(torch, lambda i: g.replay(), n_samples, warm=10)
+        st = stats_us(ms, per=a.layers)
+        by, fl = attention_algorithmic(a.wl)
+        row = {"workload": a.text, "us_per_launch_median": st["median_us"], "us_per_launch_min": st["min_us"],
+               "samples": st["samples"], "launches_per_sample": a.layers, "algorithmic_bytes": by,
+               "algorithmic_flops": fl, "traffic": traffic_on_file(name)}
+        row.update(fractions(by, fl, st["median_us"], peaks))
+        rows[name] = row
+        del a, g
+        torch.cuda.empty_cache()
+    return rows
+
+
+def cpu_baseline(wl_name, layers, attn_budget_s=10.0):
+    """The oracle as it stands, timed on the host cores over a bounded sample of the same workload and scaled to
+    one whole step.  Attention (nearly all of a step's CPU time) is timed per (sequence, layer) unit, all heads
+    and rows of the sequence, until the budget is spent, and scaled by the rows x keys of the units not run;
+    mask, tree tensors, gather and posterior run once over the full batch; the commit runs over one layer (all
+    layers if the caches are small) and is scaled by the layer count."""
     import numpy as np
     import oracle
-    from paper_2603_08088_amd import synth
-    if wl_name == "c2":
-        wl, att_layers, note = synth.config2(), layers, f"one full step of config 2: mask + tree tensorization + {layers} attention layers + gather + posterior + commit over {layers} layers"
-    else:
-        wl, _ = make_host_workload(wl_name)
-        return None
-    kt, vt = np.broadcast_to(wl.kt, (layers,) + wl.kt.shape).copy(), np.broadcast_to(wl.vt, (layers,) + wl.vt.shape).copy()
-    kc = np.broadcast_to(wl.k_cache, (layers,) + wl.k_cache.shape).copy()
-    vc = np.broadcast_to(wl.v_cache, (layers,) + wl.v_cache.shape).copy()
-    def one_step():
-        m = oracle.build_tree_mask(wl.parent, wl.n_nodes)
-        tz = oracle.tensorize_tree(wl.parent, wl.n_nodes, wl.prefix_len, wl.retrieve.shape[1], wl.W)
-        assert np.array_equal(tz["retrieve"], wl.retrieve)
-        for _ in range(att_layers):
-            oracle.tree_verify_attention(wl.q, wl.k_cache, wl.v_cache, wl.prefix_len, wl.kt, wl.vt, m["dense"],
-                                         wl.n_nodes, dtype=wl.dtype, block_table=wl.block_table, want_lse=False)
-        oracle.safe_gather_paths(wl.retrieve, wl.n_nodes, wl.T_max, 0, wl.tokens.reshape(wl.B, wl.T_max, 1))
-        p = oracle.evaluate_posterior(wl.logits, wl.tokens, wl.retrieve, wl.n_nodes)
-        oracle.commit_accepted_kv(kt, vt, kc.copy(), vc.copy(), wl.prefix_len, wl.capacity, wl.n_nodes, p["acc_nodes"],
-                                  p["accept_len"], block_table=wl.block_table)
-    # whole steps until about ten seconds of CPU work are on the clock (at most 16 steps)
-    n_steps, t0 = 0, time.perf_counter()
-    while n_steps < 16 and (n_steps == 0 or time.perf_counter() - t0 < 10.0):
-        one_step()
-        n_steps += 1
-    secs = time.perf_counter() - t0
-    return {"value": n_steps * float(wl.n_nodes.sum()) / secs, "unit": "tokens/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "sample": f"{n_steps} x " + note, "seconds": secs}
+    wl, _ = make_host_workload(wl_name, with_cache=True)
+    B = wl.B
+    t0 = time.perf_counter()
+    m = oracle.build_tree_mask(wl.parent, wl.n_nodes)
+    tz = oracle.tensorize_tree(wl.parent, wl.n_nodes, wl.prefix_len, wl.retrieve.shape[1], wl.W)
+    assert np.array_equal(tz["retrieve"], wl.retrieve)
+    t_tree = time.perf_counter() - t0
+    work = [int(wl.n_nodes[b]) * (int(wl.prefix_len[b]) + int(wl.n_nodes[b])) for b in range(B)]
+    done_work, units, t_attn = 0, 0, 0.0
+    while units < B * layers and (units == 0 or t_attn < attn_budget_s):
+        b = units % B
+        sl = slice(b, b + 1)
+        t1 = time.perf_counter()
+        oracle.tree_verify_attention(wl.q[sl], wl.k_cache if wl.paged else wl.k_cache[sl],
+                                     wl.v_cache if wl.paged else wl.v_cache[sl], wl.prefix_len[sl], wl.kt[sl], wl.vt[sl],
+                                     m["dense"][sl], wl.n_nodes[sl], dtype=wl.dtype,
+                                     block_table=wl.block_table[sl] if wl.paged else None, want_lse=False)
+        t_attn += time.perf_counter() - t1
+        done_work += work[b]
+        units += 1
+    attn_step = t_attn * (layers * sum(work)) / done_work
+    t0 = time.perf_counter()
+    oracle.safe_gather_paths(wl.retrieve, wl.n_nodes, wl.T_max, 0, wl.tokens.reshape(B, wl.T_max, 1))
+    p = oracle.evaluate_posterior(wl.logits, wl.tokens, wl.retrieve, wl.n_nodes)
+    t_post = time.perf_counter() - t0
+    cl = layers if layers * wl.k_cache.nbytes <= 2 ** 30 else 1
+    kt = np.broadcast_to(wl.kt, (cl,) + wl.kt.shape).copy()
+    vt = np.broadcast_to(wl.vt, (cl,) + wl.vt.shape).copy()
+    kc = np.broadcast_to(wl.k_cache, (cl,) + wl.k_cache.shape).copy()
+    vc = np.broadcast_to(wl.v_cache, (cl,) + wl.v_cache.shape).copy()
+    t0 = time.perf_counter()
+    oracle.commit_accepted_kv(kt, vt, kc, vc, wl.prefix_len, wl.capacity, wl.n_nodes, p["acc_nodes"], p["accept_len"],
+                              block_table=wl.block_table)
+    t_commit = (time.perf_counter() - t0) * layers / cl
+    step = t_tree + attn_step + t_post + t_commit
+    exact = units >= B * layers and cl == layers
+    return {"value": float(wl.n_nodes.sum()) / step, "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "extrapolated": not exact,
+            "sample": f"{wl_name}: oracle attention on {units} of {B * layers} (sequence, layer) units "
+                      f"({t_attn:.1f} s, scaled by rows x keys to {attn_step:.1f} s per step); mask + tree tensors "
+                      f"({t_tree:.2f} s), gather + posterior ({t_post:.2f} s) on the full batch; commit over {cl} of "
+                      f"{layers} layers (scaled: {t_commit:.2f} s)",
+            "seconds": t_tree + t_attn + t_post + t_commit * cl / layers, "step_seconds_estimate": step}
 
 
 def main():
@@ -223,6 +392,7 @@ def main():
     from paper_2603_08088_amd import api
     api.lib()   # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    n_samples = max(50, a.samples)
     wl, desc_text = make_host_workload(a.workload)
     st = Step(wl, a.layers, a.sets, a.kv_split, a.attn_flags)
     tokens_per_step = int(wl.n_nodes.sum())
@@ -253,51 +423,58 @@ def main():
     assert accept == [d for _, d in wl.planted], (accept, wl.planted)
     assert int(st.commit_out["status"].abs().sum().item()) == 0 and int(st.mask_out["status"].abs().sum().item()) == 0
 
-    # dominant kernel: one tree_verify_attention launch per layer.  Time L launches back to back between
-    # HIP events on the launch stream (captured as a graph of attention launches only).
-    att = [st.capture(lambda s=s: st.attention_layers(s)) for s in range(st.nsets)] if not a.no_graph else None
-    reps = max(3, min(50, a.steps // 4))
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for i in range(3):
-        (att[i % st.nsets].replay() if att else st.attention_layers(i % st.nsets))
-    torch.cuda.synchronize()
-    e0.record()
-    for i in range(reps):
-        (att[i % st.nsets].replay() if att else st.attention_layers(i % st.nsets))
-    e1.record()
-    torch.cuda.synchronize()
-    att_us = e0.elapsed_time(e1) * 1e3 / (reps * a.layers)
+    # median / minimum over event-timed replays: the whole step and its parts (each part its own graph)
+    timing = {"whole_step": stats_us(event_samples(torch, lambda i: runners[i % st.nsets](), n_samples))}
+    # dominant kernel: one tree_verify_attention launch per layer.  A sample = the step's `layers` launches back to
+    # back between HIP events on the launch stream (captured as a graph of attention launches only).
+    if not a.no_graph:
+        att = [st.capture(lambda s=s: st.attention_layers(s)) for s in range(st.nsets)]
+        att_fn = lambda i: att[i % st.nsets].replay()
+        g_tree = st.capture(lambda: api.tensorize_tree(st.parent, st.n_nodes, st.prefix_len, st.L_max, st.W, out=st.mask_out))
+        g_epi = st.capture(lambda: st.epilogue(0))
+        timing["tensorize_tree"] = stats_us(event_samples(torch, lambda i: g_tree.replay(), n_samples))
+        timing["verify_epilogue"] = stats_us(event_samples(torch, lambda i: g_epi.replay(), n_samples))
+    else:
+        att_fn = lambda i: st.attention_layers(i % st.nsets)
+    att_ms = event_samples(torch, att_fn, n_samples)
+    att_stats = stats_us(att_ms, per=a.layers)
+    timing["tree_verify_attention_per_launch"] = att_stats
+    att_us = att_stats["mean_us"]
     by, fl = attention_algorithmic(wl)
-    # what plain streaming loads sustain on this machine (a 1 GiB buffer read by the library's probe kernel)
-    probe = torch.empty(2 ** 30, dtype=torch.uint8, device="cuda:0").fill_(1)
-    sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
-    for _ in range(2):
-        api.hbm_read_probe(probe, sink)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(5):
-        api.hbm_read_probe(probe, sink)
-    e1.record()
-    torch.cuda.synchronize()
-    stream_gbs = 5 * probe.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del probe
+    peaks = {} if a.no_probes else run_probes(torch)
     hbm_t, mfma_t = by / (HBM_PEAK_GBS * 1e9), fl / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     if hbm_t >= mfma_t:
         roof = {"bound": "hbm", "achieved": by / (att_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
         roof = {"bound": "mfma", "achieved": fl / (att_us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
-    tpath = os.path.join(ROOT, "profiles", f"attention_hbm_traffic_{a.workload}.txt")
-    if os.path.exists(tpath):
-        roof["traffic"] = json.load(open(tpath)).get("hbm_bytes_per_launch")
-    roof.update({"kernel": "tree_verify_attention (one layer: split-KV partial kernel + combine)",
-                 "avg_launch_us": att_us, "algorithmic_bytes": by, "algorithmic_flops": fl,
+    roof["traffic"] = traffic_on_file(a.workload)
+    roof.update({"kernel": "tree_verify_attention (one layer; attn_mfma_kernel, plus attn_combine_kernel when the keys are split)",
+                 "avg_launch_us": att_us, "median_launch_us": att_stats["median_us"], "min_launch_us": att_stats["min_us"],
+                 "launches_timed": n_samples * a.layers, "algorithmic_bytes": by, "algorithmic_flops": fl,
                  "hbm_gbs": by / (att_us * 1e-6) / 1e9, "mfma_tflops": fl / (att_us * 1e-6) / 1e12,
-                 "measured_stream_read_gbs": stream_gbs})
+                 "hbm_frac": by / (att_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                 "mfma_frac": fl / (att_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS})
+    if peaks:
+        roof.update({"measured_stream_read_gbs": peaks["stream_gbs"],
+                     "measured_mfma_tflops": {"first_launch": peaks["mfma_first_launch_tflops"],
+                                              "best_launch": peaks["mfma_best_launch_tflops"],
+                                              "sustained": peaks["mfma_sustained_tflops"], "how": peaks["mfma_probe"]},
+                     "hbm_frac_of_measured": roof["hbm_gbs"] / peaks["stream_gbs"],
+                     "mfma_frac_of_measured": roof["mfma_tflops"] / peaks["mfma_sustained_tflops"]})
 
+    configs = None
+    if not a.no_configs and not a.no_graph:
+        head_row = {"workload": desc_text, "us_per_launch_median": att_stats["median_us"],
+                    "us_per_launch_min": att_stats["min_us"], "samples": att_stats["samples"],
+                    "launches_per_sample": a.layers, "algorithmic_bytes": by, "algorithmic_flops": fl,
+                    "traffic": roof["traffic"]}
+        head_row.update(fractions(by, fl, att_stats["median_us"], peaks))
+        configs = configs_table(torch, api, n_samples, peaks,
+                                headline=(a.workload, head_row) if a.layers == 32 and not a.kv_split and not a.attn_flags else None)
     # beside the step (not part of it: the step takes logits as input): the teacher head fused with the greedy
     # choice on the step's node rows, a 7B-class head (D = 4096, V = the workload's vocabulary), weights packed once
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     head = None
     if not a.no_lm_head:
         Dm, V = 4096, wl.V
@@ -336,7 +513,10 @@ def main():
                 "hbm_gbs": 2 * V * Dm / (head_us * 1e-6) / 1e9,
                 "hbm_gbs_weight_pass_only": 2 * V * Dm / (pass_us * 1e-6) / 1e9,
                 "frac_of_peak": 2 * V * Dm / (head_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                "frac_of_peak_weight_pass_only": 2 * V * Dm / (pass_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+                "frac_of_peak_weight_pass_only": 2 * V * Dm / (pass_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                "flops": 2.0 * tokens_per_step * V * Dm,
+                "mfma_tflops": 2.0 * tokens_per_step * V * Dm / (head_us * 1e-6) / 1e12,
+                "mfma_frac": 2.0 * tokens_per_step * V * Dm / (head_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
         del packed
 
 
@@ -411,7 +591,8 @@ def main():
         "config": {"workload": f"{a.workload}: {desc_text}", "layers": a.layers, "tokens_per_step": tokens_per_step,
                    "launch": "eager" if a.no_graph else "hip-graph replay", "cache_sets": st.nsets,
                    "cache_bytes": st.cache_bytes, "kv_split": a.kv_split},
-        "roofline": roof, "cpu_baseline": cpu, "lm_head_argmax": head, "branch_cache": branch,
+        "roofline": roof, "cpu_baseline": cpu, "timing": timing, "configs": configs, "lm_head_argmax": head,
+        "branch_cache": branch,
     }
     print(json.dumps(line))
 

@@ -74,12 +74,6 @@ ETV_API const char *etv_version(void);
 /* hipError_t code of the most recent failed launch in this thread (0 if none). */
 ETV_API int32_t etv_last_hip_error(void);
 
-/* Measurement aid, no part of the verification step: one kernel that streams `bytes` (>= 1 MiB, 16-byte aligned)
- * of device memory through 16-byte streaming (nontemporal) loads and discards them.  Timing it gives the read bandwidth this machine
- * sustains, the practical ceiling next to the published peak for the K/V streaming of tree_verify_attention.
- * sink: 16 bytes of device memory (written only in a practically impossible case, to keep the loads alive). */
-ETV_API int32_t etv_hbm_read_probe(const void *buf, size_t bytes, void *sink, void *stream);
-
 /* ---------------------------------------------------------------------------
  * build_tree_mask - Section 3.2 "Ancestor tables", Section 3.3 "Tree attention
  * mask" and "Implementation note" (compact ancestor encoding generated on device).

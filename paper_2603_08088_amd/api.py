@@ -30,7 +30,7 @@ ATTN_FLAG_KEY_HALVES = 8
 MAX_TREE, ATTN_MAX_TREE = 256, 256
 ATTN_STATIC_WORKSPACE_BYTES = 64 << 20
 
-EXPORTS = ("etv_status_string", "etv_version", "etv_last_hip_error", "etv_hbm_read_probe", "etv_build_tree_mask",
+EXPORTS = ("etv_status_string", "etv_version", "etv_last_hip_error", "etv_build_tree_mask",
            "etv_tensorize_tree",
            "etv_tree_verify_attention_workspace_bytes", "etv_tree_verify_attention",
            "etv_tree_verify_attention_static", "etv_safe_gather_paths",
@@ -76,8 +76,6 @@ def lib():
         l.etv_status_string.argtypes = [i32]
         l.etv_version.restype = C.c_char_p
         l.etv_last_hip_error.restype = i32
-        l.etv_hbm_read_probe.restype = i32
-        l.etv_hbm_read_probe.argtypes = [vp, sz, vp, vp]
         l.etv_build_tree_mask.restype = i32
         l.etv_build_tree_mask.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp]
         l.etv_tensorize_tree.restype = i32
@@ -139,12 +137,6 @@ def _dtype_code(t: torch.Tensor) -> int:
 
 
 # ------------------------------------------------------------------------------------------------
-def hbm_read_probe(buf: torch.Tensor, sink: torch.Tensor) -> None:
-    """Stream `buf` (any dtype, >= 1 MiB) once through plain loads; `sink` is a 16-byte device tensor."""
-    rc = lib().etv_hbm_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream())
-    _check("etv_hbm_read_probe", rc)
-
-
 def build_tree_mask(parent: torch.Tensor, n_nodes: torch.Tensor, *, want_dense: bool = True,
                     want_depth: bool = True, out: Optional[Dict[str, torch.Tensor]] = None):
     """parent int32 [B,T_max], n_nodes int32 [B] -> bitmask u64-as-int64 [B,T_max,words], dense u8

@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libeagletv.so")
+PROBE_LIB = os.path.join(HERE, "libeagletv_probe.so")   # measurement aids (include/eagletv_probe.h), separate on purpose
 SOURCES = ["api.hip", "mask.hip", "attention.hip", "posterior.hip", "commit.hip", "lmhead.hip", "branch.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
@@ -16,9 +17,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvi
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def build(verbose: bool = False, extra=()) -> str:
+def _hipcc(sources, target, verbose, extra=()):
     # extern "C" entry points are exported explicitly; everything else stays hidden
-    cmd = [HIPCC] + FLAGS + ["-DETV_BUILDING"] + list(extra) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+    cmd = [HIPCC] + FLAGS + ["-DETV_BUILDING"] + list(extra) + [os.path.join(CSRC, s) for s in sources] + ["-o", target]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -27,6 +28,11 @@ def build(verbose: bool = False, extra=()) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose: bool = False, extra=()) -> str:
+    _hipcc(SOURCES, LIB, verbose, extra)
+    _hipcc(["probe.hip"], PROBE_LIB, verbose)
     return LIB
 
 

@@ -5,33 +5,6 @@ namespace etv {
 thread_local int32_t g_last_hip_error = 0;
 }
 
-namespace etv {
-// Streaming read of a buffer with 16-byte nontemporal loads, 8 in flight per lane: what a read-once stream
-// achieves on this machine (7.1 TB/s; plain loads that allocate in L2 reach 6.0-6.4 TB/s), the practical ceiling
-// for the K/V streaming of the attention kernel.
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-__global__ void __launch_bounds__(256) hbm_read_probe_kernel(const u32x4 *__restrict__ src, size_t n16, u32x4 *sink) {
-    const size_t per_wg = n16 / gridDim.x;
-    const u32x4 *p = src + per_wg * blockIdx.x;
-    u32x4 acc = {0, 0, 0, 0};
-    for (size_t i = threadIdx.x; i + 7 * 256 < per_wg; i += 256 * 8) {
-        u32x4 v[8];
-#pragma unroll
-        for (int u = 0; u < 8; u++) v[u] = __builtin_nontemporal_load(p + i + u * 256);
-#pragma unroll
-        for (int u = 0; u < 8; u++) acc ^= v[u];
-    }
-    if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u && acc.z == 0x0fedcba9u) sink[0] = acc;  // keeps the loads alive
-}
-}  // namespace etv
-
-extern "C" int32_t etv_hbm_read_probe(const void *buf, size_t bytes, void *sink, void *stream) {
-    if (!buf || !sink || bytes < (size_t)1 << 20 || ((uintptr_t)buf & 15) || ((uintptr_t)sink & 15)) return ETV_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(etv::hbm_read_probe_kernel, dim3(4096), dim3(256), 0, etv::as_stream(stream),
-                       static_cast<const etv::u32x4 *>(buf), bytes / 16, static_cast<etv::u32x4 *>(sink));
-    return etv::check_launch();
-}
-
 extern "C" const char *etv_version(void) { return "eagletv 0.1 (gfx950)"; }
 
 extern "C" int32_t etv_last_hip_error(void) { return etv::g_last_hip_error; }

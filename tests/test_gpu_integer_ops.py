@@ -263,16 +263,21 @@ def test_commit_fully_accepted_chain_and_aliasing_prefix_len():
     assert plen.item() == P + T and np.array_equal(bits_of(got["slot_map"]), ref["slot_map"])
 
 
-def test_hbm_read_probe_runs_and_rejects_bad_arguments():
+def test_probe_library_runs_and_rejects_bad_arguments():
+    """The measurement aids (their own library): the stream probe only reads, the MFMA probe touches no memory."""
+    from paper_2603_08088_amd import probe
     buf = torch.ones(8 * 2 ** 20, dtype=torch.uint8, device="cuda:0")
     sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
-    api.hbm_read_probe(buf, sink)
+    probe.hbm_read_probe(buf, sink)
+    probe.mfma_bf16_probe(4, sink)
     torch.cuda.synchronize()
-    assert int(sink.sum().item()) == 0          # the probe only reads
-    with pytest.raises(api.EtvError):
-        api.hbm_read_probe(buf[: 2 ** 16], sink)   # below the 1 MiB minimum
-    with pytest.raises(api.EtvError):
-        api.hbm_read_probe(buf[1:], sink)          # misaligned
+    assert int(sink.sum().item()) == 0
+    with pytest.raises(RuntimeError):
+        probe.hbm_read_probe(buf[: 2 ** 16], sink)   # below the 1 MiB minimum
+    with pytest.raises(RuntimeError):
+        probe.hbm_read_probe(buf[1:], sink)          # misaligned
+    with pytest.raises(RuntimeError):
+        probe.mfma_bf16_probe(0, sink)
 
 
 def _epilogue_case(wl, L=2, dummy=0, spoil=None):

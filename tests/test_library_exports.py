@@ -8,10 +8,10 @@ from paper_2603_08088_amd import api
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "eagletv.h")).read()
+def _declared_symbols(header="eagletv.h", prefix="etv_"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(etv_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(" + prefix + r"[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported_and_binding_lists_them_all():
@@ -22,6 +22,18 @@ def test_header_symbols_are_exported_and_binding_lists_them_all():
     for s in syms:
         assert hasattr(lib, s), s
     assert sorted(api.EXPORTS) == syms
+
+
+def test_probe_library_exports_its_header_and_the_product_library_holds_no_probe():
+    from paper_2603_08088_amd import probe
+    syms = _declared_symbols("eagletv_probe.h", "etvp_")
+    assert sorted(probe.EXPORTS) == syms and len(syms) == 3
+    lib = ctypes.CDLL(probe.LIB_PATH)
+    for s in syms:
+        assert hasattr(lib, s), s
+    assert probe.mfma_bf16_probe_flops(1) == 2048 * 4 * 16 * 2 * 32 * 32 * 16
+    product = ctypes.CDLL(api.LIB_PATH)
+    assert not hasattr(product, "etv_hbm_read_probe") and not hasattr(product, "etvp_hbm_read_probe")
 
 
 def test_host_only_calls_need_no_gpu():
