@@ -463,7 +463,11 @@ int orc_evaluate_posterior(const float *logits, const int32_t *tokens, const int
  * row of node j already sits at logical position P + j of the cache itself,
  * and the same gather by path_indices is taken over the cache alone (from a
  * snapshot, so no row is read after it has been overwritten).  The tail must
- * fit: P + n_nodes > capacity is a CAPACITY failure.
+ * fit: P + n_nodes > capacity is a CAPACITY failure.  The tail was appended in
+ * node order, so an accepted root-to-leaf path reads it front to back: its node
+ * indices must increase strictly (acc_nodes[i] > acc_nodes[i-1], which holds for
+ * every path of a tree numbered parents-first); a path that does not is refused
+ * as BAD_NODE like any other inconsistent index, the sequence left untouched.
  * ---------------------------------------------------------------------- */
 int orc_commit_accepted_kv(int B, int T_max, int Hkv, int d, int elem_bytes, int n_layers, const void *kt,
                            const void *vt, void *k_cache, void *v_cache, size_t cache_layer_stride,
@@ -481,6 +485,8 @@ int orc_commit_accepted_kv(int B, int T_max, int Hkv, int d, int elem_bytes, int
             for (int i = 0; i <= A; i++) {
                 int32_t nd = acc_nodes[(size_t)b * W + i];
                 if (nd < 0 || nd >= n) st |= ORC_COMMIT_BAD_NODE;
+                /* in place: the path must walk the appended tail front to back */
+                if (!kt && i > 0 && nd <= acc_nodes[(size_t)b * W + i - 1]) st |= ORC_COMMIT_BAD_NODE;
             }
             if ((long)P + A + 1 > (long)capacity[b]) st |= ORC_COMMIT_CAPACITY;
             if (!kt && (long)P + n > (long)capacity[b]) st |= ORC_COMMIT_CAPACITY;

@@ -193,3 +193,58 @@ def test_in_place_commit_needs_room_for_the_tail():
     r = oracle.commit_accepted_kv(None, None, kc, vc, wl.prefix_len, cap, wl.n_nodes, acc, [0, 0], T_max=9)
     assert r["status"].tolist() == [0, 1] and int(r["prefix_len_out"][1]) == 12
     assert np.array_equal(kc[:, 1], before[:, 1])
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_in_place_commit_of_a_long_gapped_path_equals_fancy_indexing_of_the_tail(paged):
+    """A deep accepted path (A = 23, more than sixteen rows) with gaps, so that late sources lie just above early
+    destinations: position P+i must end up holding what position P+acc[i] held before, for every layer, head, K and V
+    (numpy fancy indexing of a snapshot of the logical rows), and nothing else in the prefix moves."""
+    rng = np.random.default_rng(41)
+    B, T = 2, 40
+    wl, kt, vt, kc, vc = _tail_workload(rng, B, T, [21, 64], paged)
+    acc = np.zeros((B, T), dtype=np.int32)
+    acc[0, :24] = np.array([0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 17, 18, 20, 23, 27, 31, 36, 39])
+    acc[1, :24] = np.arange(0, 24) + np.repeat([0, 5, 16], 8)       # 0..7, 13..20, 32..39
+    A = np.array([23, 23], dtype=np.int32)
+    n = np.array([T, T], dtype=np.int32)
+
+    def logical_rows(c, b, count):
+        P = int(wl.prefix_len[b])
+        if paged:
+            pos = np.arange(P + count)
+            return c[:, wl.block_table[b, pos // synth.BLOCK], :, pos % synth.BLOCK].copy()   # [pos, Lyr, Hkv, d]
+        return np.moveaxis(c[:, b, :P + count], 1, 0).copy()
+    before = [(logical_rows(kc, b, T), logical_rows(vc, b, T)) for b in range(B)]
+    r = oracle.commit_accepted_kv(None, None, kc, vc, wl.prefix_len, wl.capacity, n, acc, A,
+                                  block_table=wl.block_table, T_max=T)
+    assert r["status"].tolist() == [0, 0]
+    for b in range(B):
+        P = int(wl.prefix_len[b])
+        assert int(r["prefix_len_out"][b]) == P + 24
+        idx = np.concatenate([np.arange(P), P + acc[b, :24]])
+        assert np.array_equal(logical_rows(kc, b, 24), before[b][0][idx])
+        assert np.array_equal(logical_rows(vc, b, 24), before[b][1][idx])
+
+
+def test_in_place_commit_refuses_a_path_that_does_not_walk_the_tail_front_to_back():
+    """In place, the tail was appended in node order and a root-to-leaf path of a parents-first numbering reads it
+    with strictly increasing indices.  A path that goes back (or repeats a node) is refused like any other
+    inconsistent index: status bit, sequence untouched; the same indices are fine from a separate tree buffer."""
+    rng = np.random.default_rng(42)
+    wl, kt, vt, kc, vc = _tail_workload(rng, 3, 9, [10, 12, 5], False)
+    before_k, before_v = kc.copy(), vc.copy()
+    acc = np.zeros((3, 9), dtype=np.int32)
+    acc[0, :3] = [0, 4, 2]          # goes back
+    acc[1, :3] = [0, 3, 3]          # repeats
+    acc[2, :3] = [0, 2, 7]          # increasing: accepted
+    A = np.array([2, 2, 2], dtype=np.int32)
+    n = np.array([9, 9, 9], dtype=np.int32)
+    r = oracle.commit_accepted_kv(None, None, kc, vc, wl.prefix_len, wl.capacity, n, acc, A, T_max=9)
+    assert r["status"].tolist() == [2, 2, 0]
+    assert r["prefix_len_out"].tolist() == [10, 12, 8] and np.all(r["slot_map"][:2] == -1)
+    assert np.array_equal(kc[:, :2], before_k[:, :2]) and np.array_equal(vc[:, :2], before_v[:, :2])
+    assert np.array_equal(kc[:, 2, 5:8], before_k[:, 2, [5, 7, 12]])
+    kc2, vc2 = before_k.copy(), before_v.copy()
+    r2 = oracle.commit_accepted_kv(kt, vt, kc2, vc2, wl.prefix_len, wl.capacity, n, acc, A)
+    assert r2["status"].tolist() == [0, 0, 0]
