@@ -59,7 +59,7 @@ extern "C" {
 
 /* status bits written by etv_commit_accepted_kv */
 #define ETV_COMMIT_CAPACITY 1  /* prefix_len + accept_len + 1 exceeds capacity[b] (or the block table) */
-#define ETV_COMMIT_BAD_NODE 2  /* an accepted node index is not a valid node row                       */
+#define ETV_COMMIT_BAD_NODE 2  /* an accepted node index is not a valid node row (in place: or not increasing) */
 #define ETV_COMMIT_BAD_LEN 4   /* accept_len outside [0, W-1]                                          */
 #define ETV_COMMIT_BAD_BLOCK 8 /* a needed block-table entry is outside [0, num_blocks)                */
 /* additional status bits of etv_replicate_branches */
@@ -256,7 +256,9 @@ ETV_API int32_t etv_evaluate_posterior(const float *logits, const int32_t *token
  *  kt, vt       [n_layers, B, T_max, Hkv, d]; both NULL: in-place branch cache -- the tree rows are in the cache
  *               at positions prefix_len[b] + node, and the accepted ones are compacted to prefix_len[b] + i
  *               (path-index commit over the cache alone; needs prefix_len[b] + n_nodes[b] <= capacity[b], else
- *               ETV_COMMIT_CAPACITY; prefix_len_out must not alias prefix_len)
+ *               ETV_COMMIT_CAPACITY, and an accepted path whose node indices increase strictly -- the tail was
+ *               written in node order and every root-to-leaf path of a tree numbered parents-first reads it front
+ *               to back -- else ETV_COMMIT_BAD_NODE; prefix_len_out must not alias prefix_len)
  *  k_cache/v_cache: layer l starts cache_layer_stride elements after layer l-1; per-layer layout as in attention
  *  prefix_len, capacity, n_nodes, accept_len int32 [B]; acc_nodes int32 [B, W]
  *  prefix_len_out int32 [B] (may alias prefix_len); slot_map int32 [B, W]; status int32 [B]
@@ -315,16 +317,18 @@ ETV_API size_t etv_lm_head_packed_bytes(int32_t V, int32_t D);
 ETV_API int32_t etv_pack_lm_head(const void *weight, int32_t V, int32_t D, void *packed, void *stream);
 
 /* ---------------------------------------------------------------------------
- * verify_epilogue -- everything after the teacher forward in three launches
- * instead of five: the safe gather (Section 3.2 "Dummy-root indexing"), greedy
- * acceptance (Sections 2.3 and 5.1) and the commit of the accepted rows
- * (Section 3.1 "Commit by path indices and prefix-sharing fast reorder"), with
- * the accepted length and nodes staying on the device between them.  Arguments,
- * layouts, outputs and status bits are those of etv_safe_gather_paths,
- * etv_evaluate_posterior and etv_commit_accepted_kv called in that order with
- * W = h_desc->W as the row length of retrieve, acc_nodes and slot_map; the
- * results are identical.  safe, pvalid and (src, gathered) are nullable as there;
- * logits may be NULL as there (argmax is then an input).
+ * verify_epilogue -- everything after the teacher forward in one launch (two when
+ * the logits have to be scanned first): the safe gather (Section 3.2 "Dummy-root
+ * indexing"), greedy acceptance (Sections 2.3 and 5.1) and the commit of the
+ * accepted rows for all layers (Section 3.1 "Commit by path indices and
+ * prefix-sharing fast reorder"), with the accepted length and nodes never leaving
+ * the device.  Arguments, layouts, outputs and status bits are those of
+ * etv_safe_gather_paths, etv_evaluate_posterior and etv_commit_accepted_kv called
+ * in that order with W = h_desc->W as the row length of retrieve, acc_nodes and
+ * slot_map; the results are identical.  safe, pvalid and (src, gathered) are
+ * nullable as there; logits may be NULL as there (argmax is then an input).
+ * Unlike etv_commit_accepted_kv, prefix_len_out must not alias prefix_len
+ * (ETV_ERR_INVALID_ARG): several workgroups of the launch still read the old length.
  * workspace: etv_evaluate_posterior_workspace_bytes(B, T_max, V) bytes.
  * Requires T_max <= ETV_MAX_TREE and W <= ETV_MAX_TREE.
  * ------------------------------------------------------------------------- */

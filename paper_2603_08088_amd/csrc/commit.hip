@@ -17,12 +17,12 @@ __global__ void commit_plan_kernel(etv_commit_desc dsc, const int32_t *__restric
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= dsc.B) return;
     commit_plan_for_sequence(dsc, b, block_table, prefix_len[b], capacity[b], clampi(n_nodes[b], 0, dsc.T_max),
-                             acc_nodes + (size_t)b * dsc.W, accept_len[b], prefix_len_out, slot_map, status,
-                             in_place != 0);
+                             acc_nodes + (size_t)b * dsc.W, accept_len[b], prefix_len_out + b,
+                             slot_map + (size_t)b * dsc.W, status + b, in_place != 0);
 }
 
-// grid (W, B, n_layers), 256 threads: one appended position of one sequence in one layer.
-// The tree row [Hkv, d] is contiguous; 16-byte units are spread over the threads, K then V.
+// grid (W, B, n_layers), 256 threads: one appended position of one sequence in one layer, 16-byte units spread
+// over the threads, K then V.
 __global__ void __launch_bounds__(256) commit_copy_kernel(etv_commit_desc dsc, const uint8_t *__restrict__ kt,
                                                           const uint8_t *__restrict__ vt, uint8_t *__restrict__ k_cache,
                                                           uint8_t *__restrict__ v_cache,
@@ -32,36 +32,11 @@ __global__ void __launch_bounds__(256) commit_copy_kernel(etv_commit_desc dsc, c
     const int slot = slot_map[(size_t)b * dsc.W + i];
     if (slot < 0) return;
     const int node = acc_nodes[(size_t)b * dsc.W + i];
-    const size_t head_bytes = (size_t)dsc.d * dsc.elem_bytes;
-    const size_t row_bytes = head_bytes * dsc.Hkv;
-    const int units_per_head = (int)(head_bytes / 16);
-    const int units = units_per_head * dsc.Hkv;
-    const size_t src_off = (((size_t)l * dsc.B + b) * dsc.T_max + node) * row_bytes;
-    const size_t layer_off = (size_t)l * (size_t)dsc.cache_layer_stride * dsc.elem_bytes;
-    for (int u = threadIdx.x; u < 2 * units; u += 256) {
-        const bool is_v = u >= units;
-        const int uu = is_v ? u - units : u;
-        const int hh = uu / units_per_head, part = uu - hh * units_per_head;
-        size_t dst_off;
-        if (dsc.block_size > 0) {
-            int blk = slot / dsc.block_size, off = slot - blk * dsc.block_size;
-            dst_off = (((size_t)blk * dsc.Hkv + hh) * dsc.block_size + off) * head_bytes + (size_t)part * 16;
-        } else {
-            dst_off = (((size_t)b * dsc.P_cap + slot) * dsc.Hkv + hh) * head_bytes + (size_t)part * 16;
-        }
-        const uint8_t *src = (is_v ? vt : kt) + src_off + (size_t)uu * 16;
-        uint8_t *dst = (is_v ? v_cache : k_cache) + layer_off + dst_off;
-        *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
-    }
+    const int units2 = 2 * (int)((size_t)dsc.d * dsc.elem_bytes / 16) * dsc.Hkv;
+    for (int u = threadIdx.x; u < units2; u += 256) commit_copy_unit(dsc, b, l, node, slot, u, kt, vt, k_cache, v_cache);
 }
 
-// In-place branch cache: the accepted rows move from cache position P + acc_nodes[i] to P + i inside the cache.
-// A destination P + i can be the tail position of a node accepted earlier (acc_nodes[j] == i, j < i), never of one
-// accepted later (acc_nodes[j] >= j), so the copy is safe when every row is read before a later row is written.
-// grid (1, B, n_layers): a thread owns 16-byte columns of the [K row | V row] pair and moves them for all accepted
-// positions itself, sixteen positions per batch: all loads of a batch, then its stores.  A batch's stores land on
-// positions below every source of the following batches, and within a batch everything is read before anything
-// is written; different threads touch different bytes.
+// In-place branch cache, grid (1, B, n_layers): one layer of one sequence per workgroup (see commit_compact_layer).
 __global__ void __launch_bounds__(256) commit_compact_kernel(etv_commit_desc dsc, uint8_t *__restrict__ k_cache,
                                                              uint8_t *__restrict__ v_cache,
                                                              const int32_t *__restrict__ block_table,
@@ -71,43 +46,8 @@ __global__ void __launch_bounds__(256) commit_compact_kernel(etv_commit_desc dsc
                                                              const int32_t *__restrict__ slot_map) {
     const int b = blockIdx.y, l = blockIdx.z;
     if (slot_map[(size_t)b * dsc.W] < 0) return;  // the sequence failed a check: untouched
-    const int P = prefix_len[b], A = accept_len[b];
-    const size_t head_bytes = (size_t)dsc.d * dsc.elem_bytes;
-    const int units_per_head = (int)(head_bytes / 16);
-    const int units = units_per_head * dsc.Hkv;
-    const size_t layer_off = (size_t)l * (size_t)dsc.cache_layer_stride * dsc.elem_bytes;
-    auto slot_of = [&](int pos) {
-        return dsc.block_size > 0 ? block_table[(size_t)b * dsc.max_blocks + pos / dsc.block_size] * dsc.block_size +
-                                        pos % dsc.block_size
-                                  : pos;
-    };
-    auto offset_of = [&](int slot, int hh, int part) {
-        if (dsc.block_size > 0) {
-            const int blk = slot / dsc.block_size, off = slot - blk * dsc.block_size;
-            return (((size_t)blk * dsc.Hkv + hh) * dsc.block_size + off) * head_bytes + (size_t)part * 16;
-        }
-        return (((size_t)b * dsc.P_cap + slot) * dsc.Hkv + hh) * head_bytes + (size_t)part * 16;
-    };
-    for (int u = threadIdx.x; u < 2 * units; u += 256) {
-        const bool is_v = u >= units;
-        const int uu = is_v ? u - units : u;
-        const int hh = uu / units_per_head, part = uu - hh * units_per_head;
-        uint8_t *cache = (is_v ? v_cache : k_cache) + layer_off;
-        for (int i0 = 0; i0 <= A; i0 += 16) {
-            uint4 val[16];
-#pragma unroll
-            for (int j = 0; j < 16; j++) {
-                const int i = i0 + j;
-                if (i <= A)
-                    val[j] = *reinterpret_cast<const uint4 *>(cache + offset_of(slot_of(P + acc_nodes[(size_t)b * dsc.W + i]), hh, part));
-            }
-#pragma unroll
-            for (int j = 0; j < 16; j++) {
-                const int i = i0 + j;
-                if (i <= A) *reinterpret_cast<uint4 *>(cache + offset_of(slot_map[(size_t)b * dsc.W + i], hh, part)) = val[j];
-            }
-        }
-    }
+    commit_compact_layer(dsc, b, l, prefix_len[b], accept_len[b], acc_nodes + (size_t)b * dsc.W,
+                         slot_map + (size_t)b * dsc.W, block_table, k_cache, v_cache, threadIdx.x, 256);
 }
 
 }  // namespace etv
@@ -130,7 +70,7 @@ int32_t check_commit_args(const etv_commit_desc *h, const void *kt, const void *
     return ETV_OK;
 }
 
-int32_t launch_commit_copy(const etv_commit_desc *h, const void *kt, const void *vt, void *k_cache, void *v_cache,
+static int32_t launch_commit_copy(const etv_commit_desc *h, const void *kt, const void *vt, void *k_cache, void *v_cache,
                            const int32_t *acc_nodes, const int32_t *slot_map, hipStream_t s) {
     hipLaunchKernelGGL(commit_copy_kernel, dim3(h->W, h->B, h->n_layers), dim3(256), 0, s, *h,
                        static_cast<const uint8_t *>(kt), static_cast<const uint8_t *>(vt),
@@ -138,7 +78,7 @@ int32_t launch_commit_copy(const etv_commit_desc *h, const void *kt, const void 
     return check_launch();
 }
 
-int32_t launch_commit_compact(const etv_commit_desc *h, void *k_cache, void *v_cache, const int32_t *block_table,
+static int32_t launch_commit_compact(const etv_commit_desc *h, void *k_cache, void *v_cache, const int32_t *block_table,
                               const int32_t *prefix_len, const int32_t *acc_nodes, const int32_t *accept_len,
                               const int32_t *slot_map, hipStream_t s) {
     hipLaunchKernelGGL(commit_compact_kernel, dim3(1, h->B, h->n_layers), dim3(256), 0, s, *h,

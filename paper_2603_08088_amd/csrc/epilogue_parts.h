@@ -49,15 +49,16 @@ constexpr int kChunk = 4096;  // floats of one logit row scanned by one workgrou
 
 // Acceptance for sequence b by one workgroup of 256 threads (thread t): finish the argmax from the per-chunk
 // partials (or, with pval == nullptr, take argmax[] as given), walk every path with guarded compares, reduce to the best path (longest, lowest index on ties),
-// write argmax / len / best / accept_len / acc_nodes / bonus.  Leaves the accepted length in *s_A and the
-// accepted node row (W entries) in s_acc (both in LDS, valid after the call for every thread).
+// write argmax / len / best / accept_len / acc_nodes / bonus (unless write_out is false: a workgroup that only
+// needs the result for itself).  Leaves the accepted length in *s_A and the accepted node row (W entries) in
+// s_acc (both in LDS, valid after the call for every thread).
 // Section 2.3 / 5.1: greedy acceptance of the longest root-to-leaf prefix.
 __device__ __forceinline__ void posterior_for_sequence(
     int b, int t, const float *__restrict__ pval, const int32_t *__restrict__ pidx, int chunks,
     const int32_t *__restrict__ tokens, const int32_t *__restrict__ retrieve, int n, int T_max, int L_max, int W,
     int dummy, int32_t *__restrict__ argmax, int32_t *__restrict__ len, int32_t *__restrict__ best,
     int32_t *__restrict__ accept_len, int32_t *__restrict__ acc_nodes, int32_t *__restrict__ bonus, int32_t *s_A,
-    int32_t *s_acc) {
+    int32_t *s_acc, bool write_out = true) {
     __shared__ int32_t s_g[ETV_MAX_TREE];
     __shared__ int32_t s_tok[ETV_MAX_TREE];
     __shared__ int32_t s_len[256];
@@ -78,7 +79,7 @@ __device__ __forceinline__ void posterior_for_sequence(
                 const int32_t g = node < n ? m.i : -1;
                 s_g[node] = g;
                 s_tok[node] = tokens[(size_t)b * T_max + node];
-                argmax[(size_t)b * T_max + node] = g;
+                if (write_out) argmax[(size_t)b * T_max + node] = g;
             }
         }
     } else {
@@ -96,7 +97,7 @@ __device__ __forceinline__ void posterior_for_sequence(
             }
             s_g[node] = g;
             s_tok[node] = tokens[(size_t)b * T_max + node];
-            if (pval) argmax[(size_t)b * T_max + node] = g;
+            if (pval && write_out) argmax[(size_t)b * T_max + node] = g;
         }
     }
     __syncthreads();
@@ -113,7 +114,7 @@ __device__ __forceinline__ void posterior_for_sequence(
             cnt++;
             a = c;
         }
-        len[(size_t)b * L_max + p] = cnt;
+        if (write_out) len[(size_t)b * L_max + p] = cnt;
         if (cnt > my_len) {  // ascending p per thread: strict '>' keeps the lowest path
             my_len = cnt;
             my_path = p;
@@ -136,29 +137,32 @@ __device__ __forceinline__ void posterior_for_sequence(
     const int32_t *path = retrieve + ((size_t)b * L_max + bp) * W;
     for (int i = t; i < W; i += 256) {
         const int32_t nd = (i <= A) ? safe_index(path[i], T_max, dummy) : dummy;
-        acc_nodes[(size_t)b * W + i] = nd;
+        if (write_out) acc_nodes[(size_t)b * W + i] = nd;
         if (s_acc) s_acc[i] = nd;
     }
     if (t == 0) {
-        best[b] = bp;
-        accept_len[b] = A;
-        int32_t last = safe_index(path[A], T_max, dummy);
-        bonus[b] = s_g[last];
+        if (write_out) {
+            best[b] = bp;
+            accept_len[b] = A;
+            int32_t last = safe_index(path[A], T_max, dummy);
+            bonus[b] = s_g[last];
+        }
         if (s_A) *s_A = A;
     }
     __syncthreads();
 }
 
 // Commit plan of sequence b by one thread: validate, physical slot of every appended position, new prefix
-// length.  acc_row: the W accepted node rows of the sequence.  Section 3.1 "Commit by path indices and
-// prefix-sharing fast reorder".
-// in_place: the tree rows are in the cache tail (positions P .. P + n - 1), which must then exist as well.
+// length.  acc_row: the W accepted node rows of the sequence.  The results go to slot_row[0..W), *status_b and
+// *prefix_len_out_b (global memory or LDS).  Section 3.1 "Commit by path indices and prefix-sharing fast reorder".
+// in_place: the tree rows are in the cache tail (positions P .. P + n - 1), which must then exist as well, and
+// the accepted path must walk that tail front to back (strictly increasing node indices), which is what lets
+// the compaction run in ascending order without reading a row after it has been overwritten.
 __device__ __forceinline__ void commit_plan_for_sequence(const etv_commit_desc &dsc, int b,
                                                          const int32_t *__restrict__ block_table, int P, int cap,
                                                          int n, const int32_t *acc_row, int A,
-                                                         int32_t *__restrict__ prefix_len_out,
-                                                         int32_t *__restrict__ slot_map, int32_t *__restrict__ status,
-                                                         bool in_place = false) {
+                                                         int32_t *prefix_len_out_b, int32_t *slot_row,
+                                                         int32_t *status_b, bool in_place = false) {
     const int W = dsc.W;
     int32_t st = 0;
     if (A < 0 || A > W - 1) st |= ETV_COMMIT_BAD_LEN;
@@ -166,6 +170,7 @@ __device__ __forceinline__ void commit_plan_for_sequence(const etv_commit_desc &
         for (int i = 0; i <= A; i++) {
             int32_t nd = acc_row[i];
             if (nd < 0 || nd >= n) st |= ETV_COMMIT_BAD_NODE;
+            if (in_place && i > 0 && nd <= acc_row[i - 1]) st |= ETV_COMMIT_BAD_NODE;
         }
         if ((long)P + A + 1 > (long)cap || P < 0) st |= ETV_COMMIT_CAPACITY;
         if (in_place && (long)P + n > (long)cap) st |= ETV_COMMIT_CAPACITY;
@@ -192,19 +197,85 @@ __device__ __forceinline__ void commit_plan_for_sequence(const etv_commit_desc &
                                             pos % dsc.block_size
                                       : pos;
         }
-        slot_map[(size_t)b * W + i] = slot;
+        slot_row[i] = slot;
     }
-    status[b] = st;
-    prefix_len_out[b] = st ? P : P + A + 1;
+    *status_b = st;
+    *prefix_len_out_b = st ? P : P + A + 1;
+}
+
+// Byte offset, inside one layer of the cache, of 16-byte unit `part` of KV head hh at physical slot `slot`.
+__device__ __forceinline__ size_t cache_unit_offset(const etv_commit_desc &dsc, int b, int slot, int hh, int part) {
+    const size_t head_bytes = (size_t)dsc.d * dsc.elem_bytes;
+    if (dsc.block_size > 0) {
+        const int blk = slot / dsc.block_size, off = slot - blk * dsc.block_size;
+        return (((size_t)blk * dsc.Hkv + hh) * dsc.block_size + off) * head_bytes + (size_t)part * 16;
+    }
+    return (((size_t)b * dsc.P_cap + slot) * dsc.Hkv + hh) * head_bytes + (size_t)part * 16;
+}
+
+// One 16-byte unit u (0 .. 2 * Hkv * d * elem_bytes / 16: the K row, then the V row) of tree row `node` of
+// sequence b in layer l, copied to cache slot `slot`.  The tree row [Hkv, d] is contiguous.
+__device__ __forceinline__ void commit_copy_unit(const etv_commit_desc &dsc, int b, int l, int node, int slot, int u,
+                                                 const uint8_t *__restrict__ kt, const uint8_t *__restrict__ vt,
+                                                 uint8_t *__restrict__ k_cache, uint8_t *__restrict__ v_cache) {
+    const size_t head_bytes = (size_t)dsc.d * dsc.elem_bytes;
+    const int units_per_head = (int)(head_bytes / 16);
+    const int units = units_per_head * dsc.Hkv;
+    const bool is_v = u >= units;
+    const int uu = is_v ? u - units : u;
+    const int hh = uu / units_per_head, part = uu - hh * units_per_head;
+    const size_t src_off = (((size_t)l * dsc.B + b) * dsc.T_max + node) * (head_bytes * dsc.Hkv);
+    const size_t layer_off = (size_t)l * (size_t)dsc.cache_layer_stride * dsc.elem_bytes;
+    const uint8_t *src = (is_v ? vt : kt) + src_off + (size_t)uu * 16;
+    uint8_t *dst = (is_v ? v_cache : k_cache) + layer_off + cache_unit_offset(dsc, b, slot, hh, part);
+    *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+}
+
+// In-place branch cache, one layer of one sequence by the threads t, t + nthreads, ...: the accepted rows move
+// from cache position P + acc[i] to P + i (slot[i]).  The path is strictly increasing (checked by the plan), so
+// acc[i] >= i: a destination can be the tail position of a node accepted earlier, never of one accepted later,
+// and the move is safe when every row is read before a later row is written.  A thread owns 16-byte columns of
+// the [K row | V row] pair and moves them for all accepted positions itself, sixteen positions per batch: all
+// loads of a batch, then its stores.  A batch's stores land on positions below every source of the following
+// batches, and within a batch everything is read before anything is written; different threads touch different
+// bytes.  acc / slot: the sequence's accepted node row and slot row (global memory or LDS).
+__device__ __forceinline__ void commit_compact_layer(const etv_commit_desc &dsc, int b, int l, int P, int A,
+                                                     const int32_t *acc, const int32_t *slot,
+                                                     const int32_t *__restrict__ block_table,
+                                                     uint8_t *__restrict__ k_cache, uint8_t *__restrict__ v_cache,
+                                                     int t, int nthreads) {
+    const size_t head_bytes = (size_t)dsc.d * dsc.elem_bytes;
+    const int units_per_head = (int)(head_bytes / 16);
+    const int units = units_per_head * dsc.Hkv;
+    const size_t layer_off = (size_t)l * (size_t)dsc.cache_layer_stride * dsc.elem_bytes;
+    auto slot_of = [&](int pos) {
+        return dsc.block_size > 0 ? block_table[(size_t)b * dsc.max_blocks + pos / dsc.block_size] * dsc.block_size +
+                                        pos % dsc.block_size
+                                  : pos;
+    };
+    for (int u = t; u < 2 * units; u += nthreads) {
+        const bool is_v = u >= units;
+        const int uu = is_v ? u - units : u;
+        const int hh = uu / units_per_head, part = uu - hh * units_per_head;
+        uint8_t *cache = (is_v ? v_cache : k_cache) + layer_off;
+        for (int i0 = 0; i0 <= A; i0 += 16) {
+            uint4 val[16];
+#pragma unroll
+            for (int j = 0; j < 16; j++) {
+                const int i = i0 + j;
+                if (i <= A) val[j] = *reinterpret_cast<const uint4 *>(cache + cache_unit_offset(dsc, b, slot_of(P + acc[i]), hh, part));
+            }
+#pragma unroll
+            for (int j = 0; j < 16; j++) {
+                const int i = i0 + j;
+                if (i <= A) *reinterpret_cast<uint4 *>(cache + cache_unit_offset(dsc, b, slot[i], hh, part)) = val[j];
+            }
+        }
+    }
 }
 
 // host side, defined next to the commit kernels
 int32_t check_commit_args(const etv_commit_desc *h, const void *kt, const void *vt, const void *k_cache,
                           const void *v_cache, const int32_t *block_table);
-int32_t launch_commit_copy(const etv_commit_desc *h, const void *kt, const void *vt, void *k_cache, void *v_cache,
-                           const int32_t *acc_nodes, const int32_t *slot_map, hipStream_t s);
-int32_t launch_commit_compact(const etv_commit_desc *h, void *k_cache, void *v_cache, const int32_t *block_table,
-                              const int32_t *prefix_len, const int32_t *acc_nodes, const int32_t *accept_len,
-                              const int32_t *slot_map, hipStream_t s);
 
 }  // namespace etv

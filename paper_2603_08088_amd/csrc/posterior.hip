@@ -4,6 +4,7 @@
 // Section 2.3 / 5.1: greedy acceptance of the longest root-to-leaf prefix whose candidate tokens
 // equal the teacher's argmax at the preceding node.
 #include "epilogue_parts.h"
+#include <algorithm>
 
 namespace etv {
 
@@ -84,40 +85,68 @@ __global__ void __launch_bounds__(256) posterior_paths_kernel(
                            L_max, W, dummy, argmax, len, best, accept_len, acc_nodes, bonus, nullptr, nullptr);
 }
 
-// Fused epilogue.  Workgroups 0..B-1: acceptance of one sequence each, then its commit plan from the accepted
-// row that is still in LDS.  Workgroups B..: the safe gather, four path entries each (it depends on the path
-// table only, so it runs beside the acceptance instead of before it).  The copy of the accepted K/V rows
-// follows as a launch of its own (it wants one workgroup per row and layer).
+// Fused epilogue: gather, acceptance and commit in ONE launch.
+// Workgroups 0 .. B*G-1: sequence b = id / G, layer group g = id % G.  Every one of them runs the acceptance of
+// its sequence (a few KiB of per-node maxima and path entries, all cache hits after the first reader) and, from
+// the accepted row still in LDS, the commit plan; group 0 writes the results, and every group then moves the
+// accepted K/V rows of its own layers (g, g + G, ...).  Recomputing the small acceptance G times costs less than
+// any way of handing its result to other workgroups of the same launch (a flag in memory would cost each waiter
+// a device-scope round trip and the launch a scratch word that has to start at zero), and no workgroup ever
+// waits for another.  Workgroups B*G ..: the safe gather, four path entries each (it depends on the path table
+// only, so it runs beside the acceptance instead of before it).
 __global__ void __launch_bounds__(256) verify_epilogue_kernel(
-    etv_commit_desc dsc, const float *__restrict__ pval, const int32_t *__restrict__ pidx, int chunks,
+    etv_commit_desc dsc, int G, const float *__restrict__ pval, const int32_t *__restrict__ pidx, int chunks,
     const int32_t *__restrict__ tokens, const int32_t *__restrict__ retrieve, const int32_t *__restrict__ n_nodes,
     int L_max, int dummy, const uint8_t *__restrict__ src, size_t row_bytes, int32_t *__restrict__ safe,
     uint8_t *__restrict__ pvalid, uint8_t *__restrict__ gathered, int32_t *__restrict__ argmax,
     int32_t *__restrict__ len, int32_t *__restrict__ best, int32_t *__restrict__ accept_len,
-    int32_t *__restrict__ acc_nodes, int32_t *__restrict__ bonus, const int32_t *__restrict__ block_table,
-    const int32_t *__restrict__ prefix_len, const int32_t *__restrict__ capacity,
-    int32_t *__restrict__ prefix_len_out, int32_t *__restrict__ slot_map, int32_t *__restrict__ status,
-    int in_place) {
-    __shared__ int32_t s_A;
+    int32_t *__restrict__ acc_nodes, int32_t *__restrict__ bonus, const uint8_t *__restrict__ kt,
+    const uint8_t *__restrict__ vt, uint8_t *__restrict__ k_cache, uint8_t *__restrict__ v_cache,
+    const int32_t *__restrict__ block_table, const int32_t *__restrict__ prefix_len,
+    const int32_t *__restrict__ capacity, int32_t *__restrict__ prefix_len_out, int32_t *__restrict__ slot_map,
+    int32_t *__restrict__ status, int in_place) {
+    __shared__ int32_t s_A, s_st, s_plo;
     __shared__ int32_t s_acc[ETV_MAX_TREE];
+    __shared__ int32_t s_slot[ETV_MAX_TREE];
     const int t = threadIdx.x;
     const int T_max = dsc.T_max, W = dsc.W;
-    if ((int)blockIdx.x >= dsc.B) {  // uniform over the workgroup
+    if ((long)blockIdx.x >= (long)dsc.B * G) {  // uniform over the workgroup
         const long per_seq = (long)L_max * W;
-        const long e = ((long)blockIdx.x - dsc.B) * 4 + (t >> 6);
+        const long e = ((long)blockIdx.x - (long)dsc.B * G) * 4 + (t >> 6);
         if (e >= per_seq * dsc.B) return;
         const int b = (int)(e / per_seq);
         gather_entry(e, b, t & 63, retrieve, clampi(n_nodes[b], 0, T_max), T_max, dummy, src, row_bytes, safe, pvalid,
                      gathered);
         return;
     }
-    const int b = blockIdx.x;
+    const int b = blockIdx.x / G, g = blockIdx.x % G;
     const int n = clampi(n_nodes[b], 0, T_max);
+    const int P = prefix_len[b];  // read before group 0 can have written anything (prefix_len_out is another buffer)
     posterior_for_sequence(b, t, pval, pidx, chunks, tokens, retrieve, n, T_max, L_max, W, dummy, argmax, len, best,
-                           accept_len, acc_nodes, bonus, &s_A, s_acc);
-    if (t == 0)
-        commit_plan_for_sequence(dsc, b, block_table, prefix_len[b], capacity[b], n, s_acc, s_A, prefix_len_out,
-                                 slot_map, status, in_place != 0);
+                           accept_len, acc_nodes, bonus, &s_A, s_acc, g == 0);
+    if (t == 0) commit_plan_for_sequence(dsc, b, block_table, P, capacity[b], n, s_acc, s_A, &s_plo, s_slot, &s_st, in_place != 0);
+    __syncthreads();
+    if (g == 0) {
+        for (int i = t; i < W; i += 256) slot_map[(size_t)b * W + i] = s_slot[i];
+        if (t == 0) {
+            status[b] = s_st;
+            prefix_len_out[b] = s_plo;
+        }
+    }
+    if (s_st) return;  // refused: the sequence stays untouched
+    const int A = s_A;
+    if (in_place) {
+        for (int l = g; l < dsc.n_layers; l += G)
+            commit_compact_layer(dsc, b, l, P, A, s_acc, s_slot, block_table, k_cache, v_cache, t, 256);
+    } else {
+        const int units2 = 2 * (int)((size_t)dsc.d * dsc.elem_bytes / 16) * dsc.Hkv;
+        const int total = (A + 1) * units2;
+        for (int l = g; l < dsc.n_layers; l += G)
+            for (int idx = t; idx < total; idx += 256) {
+                const int i = idx / units2;
+                commit_copy_unit(dsc, b, l, s_acc[i], s_slot[i], idx - i * units2, kt, vt, k_cache, v_cache);
+            }
+    }
 }
 
 }  // namespace etv
@@ -205,7 +234,8 @@ extern "C" int32_t etv_verify_epilogue(const etv_commit_desc *h, const float *lo
     if (src && row_bytes == 0) return ETV_ERR_INVALID_ARG;
     if (h->T_max > ETV_MAX_TREE || h->W > ETV_MAX_TREE) return ETV_ERR_UNSUPPORTED;
     const bool in_place = (kt == nullptr);  // in-place branch cache, as in etv_commit_accepted_kv
-    if (in_place && prefix_len_out == prefix_len) return ETV_ERR_INVALID_ARG;
+    // several workgroups of the one launch read prefix_len[b] while another writes prefix_len_out[b]
+    if (prefix_len_out == prefix_len) return ETV_ERR_INVALID_ARG;
     if (h->B == 0) return ETV_OK;
     const int32_t B = h->B, T_max = h->T_max;
     hipStream_t s = etv::as_stream(stream);
@@ -230,14 +260,15 @@ extern "C" int32_t etv_verify_epilogue(const etv_commit_desc *h, const float *lo
         pidx = reinterpret_cast<int32_t *>(pval + (size_t)B * T_max * chunks);
     }
     const long gather_blocks = (safe || pvalid || gathered) ? ((long)B * L_max * h->W + 3) / 4 : 0;
-    if (gather_blocks + B > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(etv::verify_epilogue_kernel, dim3((unsigned)(B + gather_blocks)), dim3(256), 0, s, *h, pval, pidx, chunks, tokens, retrieve,
-                       n_nodes, (int)L_max, (int)dummy, static_cast<const uint8_t *>(src), row_bytes, safe, pvalid,
-                       static_cast<uint8_t *>(gathered), argmax, len, best, accept_len, acc_nodes, bonus, block_table,
-                       prefix_len, capacity, prefix_len_out, slot_map, status, in_place ? 1 : 0);
-    rc = etv::check_launch();
-    if (rc != ETV_OK) return rc;
-    if (in_place)
-        return etv::launch_commit_compact(h, k_cache, v_cache, block_table, prefix_len, acc_nodes, accept_len, slot_map, s);
-    return etv::launch_commit_copy(h, kt, vt, k_cache, v_cache, acc_nodes, slot_map, s);
+    // layer groups per sequence: enough workgroups to spread the row copies over the chip, at most one per layer
+    const int G = std::max(1, std::min((int)h->n_layers, 512 / B));
+    if (gather_blocks + (long)B * G > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(etv::verify_epilogue_kernel, dim3((unsigned)((long)B * G + gather_blocks)), dim3(256), 0, s, *h, G,
+                       pval, pidx, chunks, tokens, retrieve, n_nodes, (int)L_max, (int)dummy,
+                       static_cast<const uint8_t *>(src), row_bytes, safe, pvalid, static_cast<uint8_t *>(gathered),
+                       argmax, len, best, accept_len, acc_nodes, bonus, static_cast<const uint8_t *>(kt),
+                       static_cast<const uint8_t *>(vt), static_cast<uint8_t *>(k_cache),
+                       static_cast<uint8_t *>(v_cache), block_table, prefix_len, capacity, prefix_len_out, slot_map,
+                       status, in_place ? 1 : 0);
+    return etv::check_launch();
 }

@@ -402,3 +402,79 @@ def test_in_place_branch_cache_attention_and_commit(paged):
     for key in rc3:
         assert np.array_equal(bits_of(c3[key]), rc3[key]), key
     assert np.array_equal(bits_of(dkc3), okc3) and np.array_equal(bits_of(dvc3), ovc3)
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_in_place_commit_of_a_deep_gapped_path_and_refusal_of_a_backward_path(paged):
+    """An accepted path of 24 rows (more than one batch of sixteen) with gaps, so that sources of the second batch lie
+    just above destinations of the first, over five layers: the plain call and the fused epilogue (teacher choices
+    given per node) must leave the cache as the oracle's gather from a snapshot does.  A path that does not walk
+    the tail front to back is refused by both sides and the sequence stays untouched."""
+    rng = np.random.default_rng(91)
+    T, L = 40, 5
+    path = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 17, 18, 20, 23, 27, 31, 36, 39]
+    par = np.zeros(T, dtype=np.int32)
+    for a, c in zip(path[:-1], path[1:]):
+        par[c] = a
+    par2 = par.copy(); par2[16] = 3                        # second sequence: same spine, node 16 deeper in
+    wl = synth.assemble("deep_tail", rng, [par, par2, par], [21, 64, 5], Hq=4, Hkv=2, d=128, dtype="bf16", V=512, W=T,
+                        paged=paged, T_max=T, spare_blocks=3, tail_room=T, with_logits=False)
+    kc = np.stack([synth._values(rng, wl.k_cache.shape, "bf16") for _ in range(L)])
+    vc = np.stack([synth._values(rng, wl.v_cache.shape, "bf16") for _ in range(L)])
+    d = DevWorkload(wl)
+    acc = np.zeros((3, T), dtype=np.int32)
+    acc[0, :24] = path; acc[1, :24] = path
+    acc[2, :4] = [0, 2, 1, 3]                              # goes back: refused in place
+    A = np.array([23, 23, 3], dtype=np.int32)
+    okc, ovc = kc.copy(), vc.copy()
+    rc = oracle.commit_accepted_kv(None, None, okc, ovc, wl.prefix_len, wl.capacity, wl.n_nodes, acc, A,
+                                   block_table=wl.block_table, T_max=T)
+    assert rc["status"].tolist() == [0, 0, api.COMMIT_BAD_NODE]
+    assert not np.array_equal(okc, kc)
+    dkc, dvc = to_dev(kc), to_dev(vc)
+    c = api.commit_accepted_kv(None, None, dkc, dvc, d.prefix_len, d.capacity, d.n_nodes, to_dev(acc), to_dev(A),
+                               block_table=d.block_table, T_max=T)
+    torch.cuda.synchronize()
+    for key in rc:
+        assert np.array_equal(bits_of(c[key]), rc[key]), key
+    assert np.array_equal(bits_of(dkc), okc) and np.array_equal(bits_of(dvc), ovc)
+    # fused epilogue: the teacher's choice per node is given, planted so that the whole spine is accepted
+    g = np.full((3, T), -1, dtype=np.int32)
+    for b in range(3):
+        for a_, c_ in zip(path[:-1], path[1:]):
+            g[b, a_] = wl.tokens[b, c_]
+        g[b, path[-1]] = 7
+    g[g < 0] = 0                                           # every node has a choice; off the spine it is token 0
+    rp = oracle.evaluate_posterior(synth_logits_from(g, 512), wl.tokens, wl.retrieve, wl.n_nodes)
+    assert rp["accept_len"].tolist() == [23, 23, 23] and rp["acc_nodes"][0, :24].tolist() == path
+    okc2, ovc2 = kc.copy(), vc.copy()
+    rc2 = oracle.commit_accepted_kv(None, None, okc2, ovc2, wl.prefix_len, wl.capacity, wl.n_nodes, rp["acc_nodes"],
+                                    rp["accept_len"], block_table=wl.block_table, T_max=T)
+    assert rc2["status"].tolist() == [0, 0, 0]
+    dkc2, dvc2 = to_dev(kc), to_dev(vc)
+    _, p2, c2 = api.verify_epilogue(None, d.tokens, d.retrieve, d.n_nodes, None, None, dkc2, dvc2, d.prefix_len,
+                                    d.capacity, block_table=d.block_table, post_out=dict(argmax=to_dev(g)))
+    torch.cuda.synchronize()
+    for key in rp:
+        assert np.array_equal(bits_of(p2[key]), rp[key]), key
+    for key in rc2:
+        assert np.array_equal(bits_of(c2[key]), rc2[key]), key
+    assert np.array_equal(bits_of(dkc2), okc2) and np.array_equal(bits_of(dvc2), ovc2)
+
+
+def synth_logits_from(g, V):
+    """Logits whose row argmax is g (padding rows, g < 0: any)."""
+    lg = np.zeros(g.shape + (V,), dtype=np.float32)
+    for idx in np.ndindex(g.shape):
+        if g[idx] >= 0:
+            lg[idx][g[idx]] = 5.0
+    return lg
+
+
+def test_fused_epilogue_refuses_an_aliased_prefix_length_output():
+    wl = synth.config1()
+    d = DevWorkload(wl)
+    kc, vc = d.k_cache[None].clone(), d.v_cache[None].clone()
+    with pytest.raises(api.EtvError):
+        api.verify_epilogue(d.logits, d.tokens, d.retrieve, d.n_nodes, d.kt[None], d.vt[None], kc, vc, d.prefix_len,
+                            d.capacity, commit_out=dict(prefix_len_out=d.prefix_len))
