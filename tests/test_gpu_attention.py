@@ -5,6 +5,9 @@ fp32 accumulation.  Because outputs of flat softmaxes are small (std about sqrt(
 bounds the scaled error |gpu - ref| / (|ref| + rms(ref)) by 1e-5 (fp32) / 2e-2 (bf16; bf16 rounding of the probabilities and of
 the output alone is 2^-9 relative), and "peaked" twins (Q x 4) make the outputs O(1).
 """
+import json
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -19,6 +22,27 @@ pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-5, "bf16": 2e-2}
 REL_TOL = {"f32": 1e-5, "bf16": 2e-2}   # max of |err| / (|ref| + rms(ref))
 
+# worst observed errors per test, written as JSON to $ETV_ERROR_REPORT when that is set (a record for the
+# tolerance table of the design notes; the assertions do not depend on it)
+_WORST = {}
+
+
+def _record(tag, err, rel):
+    name = os.environ.get("PYTEST_CURRENT_TEST", "?").split("::")[-1].split(" ")[0]
+    w = _WORST.setdefault(name, {"max_abs": 0.0, "scaled": 0.0, "worst_case": ""})
+    w["max_abs"] = max(w["max_abs"], err)
+    if rel > w["scaled"]:
+        w["scaled"], w["worst_case"] = rel, tag
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _error_report():
+    yield
+    path = os.environ.get("ETV_ERROR_REPORT")
+    if path:
+        with open(path, "w") as f:
+            json.dump(_WORST, f, indent=1, sort_keys=True)
+
 
 def _check(wl, *, kv_split=0, flags=0, check_lse=True, rows=None):
     d = DevWorkload(wl)
@@ -32,6 +56,8 @@ def _check(wl, *, kv_split=0, flags=0, check_lse=True, rows=None):
                                                 block_table=wl.block_table)
     err, rel, padded_zero = attention_errors(out, ref, wl.n_nodes)
     assert padded_zero, "padded rows must be exact zeros"
+    _record(f"{wl.name} B={wl.B} T={wl.T_max} G={wl.Hq // wl.Hkv} P={wl.prefix_len.tolist()[:4]} kv_split={kv_split} flags={flags}",
+            err, rel)
     assert err <= TOL[wl.dtype], (wl.name, err)
     assert rel <= REL_TOL[wl.dtype], (wl.name, rel)
     if check_lse:
@@ -185,11 +211,16 @@ def test_unsupported_and_invalid_arguments_are_rejected():
     with pytest.raises(api.EtvError):        # P_max beyond the rows the cache holds
         api.tree_verify_attention(d.q, d.k_cache, d.v_cache, d.prefix_len, d.kt, d.vt, m["bitmask"], d.n_nodes,
                                   P_max=10 ** 6)
-    with pytest.raises(api.EtvError):        # workspace too small for a split launch
-        api.tree_verify_attention(d.q, d.k_cache, d.v_cache, d.prefix_len, d.kt, d.vt, m["bitmask"], d.n_nodes,
-                                  P_max=64, kv_split=64, workspace=torch.empty(256, dtype=torch.uint8, device="cuda")) \
-            if api.tree_verify_attention_workspace_bytes(api.attn_desc(d.q, d.kt, d.k_cache, None, 64, kv_split=64)) > 256 \
-            else (_ for _ in ()).throw(api.EtvError("etv_tree_verify_attention", -3))
+    # workspace too small for a split launch: five one-tile splits of a 300-key prefix need far more than 256 bytes
+    wl5 = _small(rng, 1, 8, 4, 2, 128, [300], "bf16", False)
+    d5 = DevWorkload(wl5)
+    m5 = api.build_tree_mask(d5.parent, d5.n_nodes)
+    need = api.tree_verify_attention_workspace_bytes(api.attn_desc(d5.q, d5.kt, d5.k_cache, None, 300, kv_split=64))
+    assert need >= 5 * 8 * 4 * 130 * 4
+    with pytest.raises(api.EtvError) as e:
+        api.tree_verify_attention(d5.q, d5.k_cache, d5.v_cache, d5.prefix_len, d5.kt, d5.vt, m5["bitmask"], d5.n_nodes,
+                                  P_max=300, kv_split=64, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.rc == -3
     q3 = torch.zeros((1, 8, 3, 128), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(api.EtvError):
         api.tree_verify_attention(q3, d.k_cache, d.v_cache, d.prefix_len, d.kt, d.vt, m["bitmask"], d.n_nodes, P_max=64)
@@ -210,48 +241,34 @@ def test_config3_ragged_batch():
     print(f"config3: max-abs {err:.3e} scaled {rel:.3e}")
 
 
-def test_config4_long_context_sampled_heads():
-    """Full-size GPU run; the oracle recomputes two KV heads (8 of 32 query heads), all 128 rows."""
+def test_config4_long_context_all_heads():
+    """Full-size run, every row of every head against the oracle."""
     wl = synth.config4(with_logits=False)
-    d = DevWorkload(wl)
-    m = api.build_tree_mask(d.parent, d.n_nodes)
-    out, _ = gpu_attention(d, m["bitmask"])
-    torch.cuda.synchronize()
-    dense = oracle.build_tree_mask(wl.parent, wl.n_nodes)["dense"]
-    G = wl.Hq // wl.Hkv
-    for kvh in (0, 5):
-        hs = slice(kvh * G, (kvh + 1) * G)
-        ref, _ = oracle.tree_verify_attention(np.ascontiguousarray(wl.q[:, :, hs]),
-                                              np.ascontiguousarray(wl.k_cache[:, :, kvh:kvh + 1]),
-                                              np.ascontiguousarray(wl.v_cache[:, :, kvh:kvh + 1]), wl.prefix_len,
-                                              np.ascontiguousarray(wl.kt[:, :, kvh:kvh + 1]),
-                                              np.ascontiguousarray(wl.vt[:, :, kvh:kvh + 1]), dense, wl.n_nodes,
-                                              dtype="bf16")
-        err, rel, _ = attention_errors(out[:, :, hs], ref, wl.n_nodes)
-        print(f"config4 kv head {kvh}: max-abs {err:.3e} scaled {rel:.3e}")
-        assert err <= 2e-2 and rel <= 2e-2
+    err, rel = _check(wl, check_lse=True)
+    print(f"config4: max-abs {err:.3e} scaled {rel:.3e}")
 
 
-@pytest.mark.parametrize("T,D", [(8, 4), (16, 10), (32, 6), (64, 8), (128, 10), (256, 16)])
-def test_config5_sweep_cells_sampled_sequences(T, D):
-    """Full batch of 32 on the GPU; the oracle recomputes 2 seeded sequences and 2 KV heads."""
+# the budget sweep: every (T, D) cell; D is clamped to T - 1 (T = 8 with D = 8 or 10 is the depth-7 cell twice)
+C5_CELLS = [(T, D) for T in (8, 16, 32, 64, 128) for D in (4, 6, 8, 10)] + [(256, 16)]
+
+
+@pytest.mark.parametrize("T,D", C5_CELLS)
+def test_config5_sweep_cells(T, D):
+    """Full batch of 32 on the GPU in the launch shape the benchmark times; the oracle recomputes every row of every
+    head of three seeded sequences (the sequences of a cell share one tree and differ in their values)."""
     wl = synth.config5(T, D, with_logits=False)
     d = DevWorkload(wl)
     m = api.build_tree_mask(d.parent, d.n_nodes)
     out, _ = gpu_attention(d, m["bitmask"])
     torch.cuda.synchronize()
-    dense = oracle.build_tree_mask(wl.parent, wl.n_nodes)["dense"]
-    G = wl.Hq // wl.Hkv
+    ref_mask = oracle.build_tree_mask(wl.parent, wl.n_nodes)
+    assert np.array_equal(bits_of(m["bitmask"]).view(np.uint64), ref_mask["bitmask"])
+    dense = ref_mask["dense"]
     rng = np.random.default_rng(T * 100 + D)
-    for b in rng.choice(wl.B, size=2, replace=False):
-        for kvh in rng.choice(wl.Hkv, size=2, replace=False):
-            hs = slice(kvh * G, (kvh + 1) * G)
-            sl = slice(b, b + 1)
-            ref, _ = oracle.tree_verify_attention(np.ascontiguousarray(wl.q[sl, :, hs]),
-                                                  np.ascontiguousarray(wl.k_cache[:, kvh:kvh + 1]),
-                                                  np.ascontiguousarray(wl.v_cache[:, kvh:kvh + 1]), wl.prefix_len[sl],
-                                                  np.ascontiguousarray(wl.kt[sl, :, kvh:kvh + 1]),
-                                                  np.ascontiguousarray(wl.vt[sl, :, kvh:kvh + 1]), dense[sl],
-                                                  wl.n_nodes[sl], dtype="bf16", block_table=wl.block_table[sl])
-            err, rel, _ = attention_errors(out[sl, :, hs], ref, wl.n_nodes[sl])
-            assert err <= 2e-2 and rel <= 2e-2, (T, D, b, kvh, err, rel)
+    for b in sorted(int(x) for x in rng.choice(wl.B, size=3, replace=False)):
+        sl = slice(b, b + 1)
+        ref, _ = oracle.tree_verify_attention(wl.q[sl], wl.k_cache, wl.v_cache, wl.prefix_len[sl], wl.kt[sl], wl.vt[sl],
+                                              dense[sl], wl.n_nodes[sl], dtype="bf16", block_table=wl.block_table[sl])
+        err, rel, padded_zero = attention_errors(out[sl], ref, wl.n_nodes[sl])
+        _record(f"{wl.name} sequence {b}", err, rel)
+        assert padded_zero and err <= TOL["bf16"] and rel <= REL_TOL["bf16"], (T, D, b, err, rel)
