@@ -321,7 +321,8 @@ def configs_table(torch, api, n_samples, peaks, headline=None):
         by, fl = attention_algorithmic(a.wl)
         row = {"workload": a.text, "us_per_launch_median": st["median_us"], "us_per_launch_min": st["min_us"],
                "samples": st["samples"], "launches_per_sample": a.layers, "algorithmic_bytes": by,
-               "algorithmic_flops": fl, "traffic": traffic_on_file(name)}
+               "algorithmic_flops": fl, "traffic": traffic_on_file(name),
+               "plan": api.tree_verify_attention_plan(a.desc)}
         row.update(fractions(by, fl, st["median_us"], peaks))
         rows[name] = row
         del a, g
@@ -449,6 +450,7 @@ def main():
         roof = {"bound": "mfma", "achieved": fl / (att_us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = traffic_on_file(a.workload)
+    roof["plan"] = api.tree_verify_attention_plan(st.desc)
     roof.update({"kernel": "tree_verify_attention (one layer; attn_mfma_kernel, plus attn_combine_kernel when the keys are split)",
                  "avg_launch_us": att_us, "median_launch_us": att_stats["median_us"], "min_launch_us": att_stats["min_us"],
                  "launches_timed": n_samples * a.layers, "algorithmic_bytes": by, "algorithmic_flops": fl,
@@ -468,7 +470,7 @@ def main():
         head_row = {"workload": desc_text, "us_per_launch_median": att_stats["median_us"],
                     "us_per_launch_min": att_stats["min_us"], "samples": att_stats["samples"],
                     "launches_per_sample": a.layers, "algorithmic_bytes": by, "algorithmic_flops": fl,
-                    "traffic": roof["traffic"]}
+                    "traffic": roof["traffic"], "plan": api.tree_verify_attention_plan(st.desc)}
         head_row.update(fractions(by, fl, att_stats["median_us"], peaks))
         configs = configs_table(torch, api, n_samples, peaks,
                                 headline=(a.workload, head_row) if a.layers == 32 and not a.kv_split and not a.attn_flags else None)

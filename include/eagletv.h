@@ -168,7 +168,28 @@ typedef struct etv_attn_desc {
 #define ETV_ATTN_FLAG_WHOLE_TILE 4 /* every wavefront takes whole 64-key tiles, never key halves (tuning) */
 #define ETV_ATTN_FLAG_KEY_HALVES 8 /* two wavefronts per 32-row chunk wherever the tree is small enough (tuning) */
 
+#define ETV_ATTN_FLAG_LARGE_WG 16 /* 8-wavefront workgroups wherever the tree has enough rows for them (tuning) */
+
 ETV_API size_t etv_tree_verify_attention_workspace_bytes(const etv_attn_desc *h_desc);
+
+/* The launch shape the library picks for h_desc (host only, launches nothing): which kernel, how many wavefronts
+ * per workgroup, whether two wavefronts share a 32-row chunk (key halves), the depth of the K/V tile ring, the row
+ * groups per (split, KV head), the keys per split and the number of splits.  The pick comes from a small cost
+ * model fitted on one machine; kv_split and the ETV_ATTN_FLAG_* tuning flags of h_desc override every part of it,
+ * and this call shows the outcome, so that a poor pick on another shape or machine can be seen and corrected. */
+typedef struct etv_attn_plan {
+    int32_t mfma;        /* 1: attn_mfma_kernel (bf16, d = 128); 0: the fp32-VALU kernel */
+    int32_t wavefronts;  /* per workgroup: 4 or 8 (1 for the VALU kernel) */
+    int32_t key_halves;  /* 1: two wavefronts per 32-row chunk, each with 32 of a tile's 64 keys */
+    int32_t ring_stages; /* K/V tiles of LDS ring */
+    int32_t row_groups;  /* workgroups per (split, KV head, sequence) */
+    int32_t kv_split;    /* prefix keys per split (multiple of 64) */
+    int32_t n_splits;    /* splits the launch provides; more than 1 means partials + the combine launch */
+    int32_t reserved;
+    int64_t workgroups;  /* grid size of the partial kernel */
+} etv_attn_plan;
+
+ETV_API int32_t etv_tree_verify_attention_plan(const etv_attn_desc *h_desc, etv_attn_plan *out);
 
 ETV_API int32_t etv_tree_verify_attention(const etv_attn_desc *h_desc, const void *q, const void *k_cache,
                                   const void *v_cache, const int32_t *block_table, const int32_t *prefix_len,

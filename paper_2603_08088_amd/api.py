@@ -27,12 +27,13 @@ ATTN_FLAG_GENERIC = 1
 ATTN_FLAG_SMALL_WG = 2
 ATTN_FLAG_WHOLE_TILE = 4
 ATTN_FLAG_KEY_HALVES = 8
+ATTN_FLAG_LARGE_WG = 16
 MAX_TREE, ATTN_MAX_TREE = 256, 256
 ATTN_STATIC_WORKSPACE_BYTES = 64 << 20
 
 EXPORTS = ("etv_status_string", "etv_version", "etv_last_hip_error", "etv_build_tree_mask",
            "etv_tensorize_tree",
-           "etv_tree_verify_attention_workspace_bytes", "etv_tree_verify_attention",
+           "etv_tree_verify_attention_workspace_bytes", "etv_tree_verify_attention_plan", "etv_tree_verify_attention",
            "etv_tree_verify_attention_static", "etv_safe_gather_paths",
            "etv_evaluate_posterior_workspace_bytes", "etv_evaluate_posterior", "etv_commit_accepted_kv",
            "etv_verify_epilogue", "etv_lm_head_argmax_workspace_bytes", "etv_lm_head_argmax",
@@ -43,6 +44,11 @@ class AttnDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "T_max", "Hq", "Hkv", "d", "dtype", "block_size", "max_blocks",
                                          "num_blocks", "P_cap", "P_max")] + \
                [("scale", C.c_float), ("kv_split", C.c_int32), ("flags", C.c_int32)]
+
+
+class AttnPlan(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("mfma", "wavefronts", "key_halves", "ring_stages", "row_groups", "kv_split",
+                                         "n_splits", "reserved")] + [("workgroups", C.c_int64)]
 
 
 class CommitDesc(C.Structure):
@@ -82,6 +88,8 @@ def lib():
         l.etv_tensorize_tree.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         l.etv_tree_verify_attention_workspace_bytes.restype = sz
         l.etv_tree_verify_attention_workspace_bytes.argtypes = [C.POINTER(AttnDesc)]
+        l.etv_tree_verify_attention_plan.restype = i32
+        l.etv_tree_verify_attention_plan.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnPlan)]
         l.etv_tree_verify_attention.restype = i32
         l.etv_tree_verify_attention.argtypes = [C.POINTER(AttnDesc)] + [vp] * 12 + [sz, vp]
         l.etv_tree_verify_attention_static.restype = i32
@@ -203,6 +211,13 @@ def attn_desc(q: torch.Tensor, kt: torch.Tensor, k_cache: Optional[torch.Tensor]
 
 def tree_verify_attention_workspace_bytes(dsc: AttnDesc) -> int:
     return int(lib().etv_tree_verify_attention_workspace_bytes(C.byref(dsc)))
+
+
+def tree_verify_attention_plan(dsc: AttnDesc) -> Dict[str, int]:
+    """The launch shape the library picks for this descriptor (host only)."""
+    pl = AttnPlan()
+    _check("etv_tree_verify_attention_plan", lib().etv_tree_verify_attention_plan(C.byref(dsc), C.byref(pl)))
+    return {n: int(getattr(pl, n)) for n, _ in AttnPlan._fields_ if n != "reserved"}
 
 
 def tree_verify_attention(q, k_cache, v_cache, prefix_len, kt, vt, bitmask, n_nodes, *, P_max: int,

@@ -1029,6 +1029,7 @@ static Plan make_plan(const etv_attn_desc *h) {
             if (kh && (h->flags & ETV_ATTN_FLAG_WHOLE_TILE)) continue;
             if (!kh && (h->flags & ETV_ATTN_FLAG_KEY_HALVES)) continue;
             if (nw == 8 && (pl.pairs <= (kh ? 2 : 4) || (h->flags & ETV_ATTN_FLAG_SMALL_WG))) continue;
+            if (nw == 4 && (h->flags & ETV_ATTN_FLAG_LARGE_WG) && pl.pairs > (kh ? 2 : 4)) continue;
             const int wgp = (pl.pairs + cw - 1) / cw;
             const long units = (long)B * h->Hkv * wgp;
             // candidates: every distinct number of splits, or the one split size the caller asks for
@@ -1074,6 +1075,21 @@ static int32_t launch_mfma(const AttnParams &p, dim3 grid, hipStream_t st) {
 }
 
 }  // namespace etv
+
+extern "C" int32_t etv_tree_verify_attention_plan(const etv_attn_desc *h, etv_attn_plan *out) {
+    if (!h || !out || !etv::supported(h) || h->Hq % h->Hkv != 0) return ETV_ERR_INVALID_ARG;
+    const etv::Plan pl = etv::make_plan(h);
+    out->mfma = pl.mfma ? 1 : 0;
+    out->wavefronts = pl.mfma ? pl.nw : 1;
+    out->key_halves = pl.mfma && pl.kh ? 1 : 0;
+    out->ring_stages = pl.mfma ? pl.ns : 0;
+    out->row_groups = pl.mfma ? pl.wgp : 0;
+    out->kv_split = pl.chunk;
+    out->n_splits = pl.nsplit;
+    out->workgroups = pl.mfma ? (int64_t)pl.nsplit * h->Hkv * pl.wgp * (h->B > 0 ? h->B : 0)
+                              : (int64_t)h->T_max * h->Hq * (h->B > 0 ? h->B : 0) * pl.nsplit;
+    return ETV_OK;
+}
 
 extern "C" size_t etv_tree_verify_attention_workspace_bytes(const etv_attn_desc *h) {
     if (!h || !etv::supported(h) || h->B == 0) return 0;

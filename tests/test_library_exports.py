@@ -49,6 +49,27 @@ def test_host_only_calls_need_no_gpu():
     assert api.evaluate_posterior_workspace_bytes(1, 60, 32000) == 60 * 8 * 8
 
 
+def test_launch_plan_is_reported_and_follows_the_tuning_flags():
+    """Host-only: the plan call shows what the cost model picks, and kv_split / the flags override it."""
+    def desc(B, T, P, paged, **kw):
+        return api.AttnDesc(B=B, T_max=T, Hq=32, Hkv=8, d=128, dtype=api.BF16, block_size=16 if paged else 0,
+                            max_blocks=(P + T + 15) // 16 + 1, num_blocks=0, P_cap=P + T, P_max=P, scale=0.0,
+                            kv_split=kw.get("kv_split", 0), flags=kw.get("flags", 0))
+    big = api.tree_verify_attention_plan(desc(32, 128, 4096, True))
+    assert big["mfma"] == 1 and big["n_splits"] == 1 and big["kv_split"] == 4096 and big["workgroups"] == 32 * 8 * big["row_groups"]
+    assert big["wavefronts"] * (1 if not big["key_halves"] else 0.5) * big["row_groups"] >= 16      # 16 chunks of 32 rows
+    c2 = api.tree_verify_attention_plan(desc(1, 60, 2048, False))
+    assert c2["n_splits"] > 1 and c2["kv_split"] % 64 == 0 and c2["kv_split"] * c2["n_splits"] >= 2048
+    forced = api.tree_verify_attention_plan(desc(1, 60, 2048, False, kv_split=512, flags=api.ATTN_FLAG_WHOLE_TILE | api.ATTN_FLAG_SMALL_WG))
+    assert forced["kv_split"] == 512 and forced["n_splits"] == 4 and forced["key_halves"] == 0 and forced["wavefronts"] == 4
+    large = api.tree_verify_attention_plan(desc(1, 60, 2048, False, flags=api.ATTN_FLAG_LARGE_WG | api.ATTN_FLAG_WHOLE_TILE))
+    assert large["wavefronts"] == 8 and large["key_halves"] == 0
+    f32 = api.AttnDesc(B=1, T_max=15, Hq=4, Hkv=4, d=64, dtype=api.F32, block_size=0, max_blocks=0, num_blocks=0,
+                       P_cap=200, P_max=128, scale=0.0, kv_split=0, flags=0)
+    assert api.tree_verify_attention_plan(f32)["mfma"] == 0
+
+
 def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(api.AttnDesc) == 14 * 4
+    assert ctypes.sizeof(api.AttnPlan) == 8 * 4 + 8
     assert ctypes.sizeof(api.CommitDesc) == 12 * 4 + 8
