@@ -431,10 +431,20 @@ def main():
     if not a.no_graph:
         att = [st.capture(lambda s=s: st.attention_layers(s)) for s in range(st.nsets)]
         att_fn = lambda i: att[i % st.nsets].replay()
-        g_tree = st.capture(lambda: api.tensorize_tree(st.parent, st.n_nodes, st.prefix_len, st.L_max, st.W, out=st.mask_out))
-        g_epi = st.capture(lambda: st.epilogue(0))
-        timing["tensorize_tree"] = stats_us(event_samples(torch, lambda i: g_tree.replay(), n_samples))
-        timing["verify_epilogue"] = stats_us(event_samples(torch, lambda i: g_epi.replay(), n_samples))
+        # the short parts: a sample is a graph of 20 calls (both are idempotent), so that the replay's own launch
+        # cost does not drown a call of a few microseconds
+        REP = 20
+
+        def tree_calls():
+            for _ in range(REP):
+                api.tensorize_tree(st.parent, st.n_nodes, st.prefix_len, st.L_max, st.W, out=st.mask_out)
+
+        def epilogue_calls():
+            for _ in range(REP):
+                st.epilogue(0)
+        g_tree, g_epi = st.capture(tree_calls), st.capture(epilogue_calls)
+        timing["tensorize_tree"] = stats_us(event_samples(torch, lambda i: g_tree.replay(), n_samples), per=REP)
+        timing["verify_epilogue"] = stats_us(event_samples(torch, lambda i: g_epi.replay(), n_samples), per=REP)
     else:
         att_fn = lambda i: st.attention_layers(i % st.nsets)
     att_ms = event_samples(torch, att_fn, n_samples)

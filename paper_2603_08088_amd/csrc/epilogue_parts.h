@@ -203,6 +203,70 @@ __device__ __forceinline__ void commit_plan_for_sequence(const etv_commit_desc &
     *prefix_len_out_b = st ? P : P + A + 1;
 }
 
+// The same plan computed by a whole workgroup (thread t of nthreads, all of them call it): one position per thread
+// instead of one thread walking all of them, because every position costs a dependent trip to the block table and
+// a single thread pays those one after the other.  The checks are those of commit_plan_for_sequence in an order
+// that does not matter: a position whose logical block lies behind the table row sets CAPACITY and skips the block
+// check, exactly the positions the sequential walk never reaches.  s_status: one word of LDS; the results are in
+// slot_row / *status_b / *prefix_len_out_b after the call's last barrier.
+__device__ __forceinline__ void commit_plan_cooperative(const etv_commit_desc &dsc, int b,
+                                                        const int32_t *__restrict__ block_table, int P, int cap, int n,
+                                                        const int32_t *acc_row, int A, int32_t *prefix_len_out_b,
+                                                        int32_t *slot_row, int32_t *status_b, bool in_place, int t,
+                                                        int nthreads, int32_t *s_status) {
+    const int W = dsc.W;
+    const bool bad_len = (A < 0 || A > W - 1);
+    int32_t pre = bad_len ? ETV_COMMIT_BAD_LEN : 0;
+    if (!bad_len) {
+        if ((long)P + A + 1 > (long)cap || P < 0) pre |= ETV_COMMIT_CAPACITY;
+        if (in_place && (long)P + n > (long)cap) pre |= ETV_COMMIT_CAPACITY;
+    }
+    if (t == 0) *s_status = pre;
+    __syncthreads();
+    if (!bad_len) {
+        int32_t mine = 0;
+        for (int i = t; i <= A; i += nthreads) {
+            const int32_t nd = acc_row[i];
+            if (nd < 0 || nd >= n) mine |= ETV_COMMIT_BAD_NODE;
+            if (in_place && i > 0 && nd <= acc_row[i - 1]) mine |= ETV_COMMIT_BAD_NODE;
+        }
+        const int reach = in_place ? max(n, A + 1) : A + 1;
+        if (!(pre & ETV_COMMIT_CAPACITY)) {
+            if (dsc.block_size > 0) {
+                for (int i = t; i < reach; i += nthreads) {
+                    const int lb = (P + i) / dsc.block_size;
+                    if (lb >= dsc.max_blocks) {
+                        mine |= ETV_COMMIT_CAPACITY;
+                    } else {
+                        const int blk = block_table[(size_t)b * dsc.max_blocks + lb];
+                        if (blk < 0 || blk >= dsc.num_blocks) mine |= ETV_COMMIT_BAD_BLOCK;
+                    }
+                }
+            } else if (t == 0 && (long)P + reach > (long)dsc.P_cap) {
+                mine |= ETV_COMMIT_CAPACITY;
+            }
+        }
+        if (mine) atomicOr(s_status, mine);
+    }
+    __syncthreads();
+    const int32_t st = *s_status;
+    for (int i = t; i < W; i += nthreads) {
+        int32_t slot = -1;
+        if (!st && i <= A) {
+            const int pos = P + i;
+            slot = dsc.block_size > 0 ? block_table[(size_t)b * dsc.max_blocks + pos / dsc.block_size] * dsc.block_size +
+                                            pos % dsc.block_size
+                                      : pos;
+        }
+        slot_row[i] = slot;
+    }
+    if (t == 0) {
+        *status_b = st;
+        *prefix_len_out_b = st ? P : P + A + 1;
+    }
+    __syncthreads();
+}
+
 // Byte offset, inside one layer of the cache, of 16-byte unit `part` of KV head hh at physical slot `slot`.
 __device__ __forceinline__ size_t cache_unit_offset(const etv_commit_desc &dsc, int b, int slot, int hh, int part) {
     const size_t head_bytes = (size_t)dsc.d * dsc.elem_bytes;

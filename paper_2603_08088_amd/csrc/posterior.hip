@@ -105,7 +105,7 @@ __global__ void __launch_bounds__(256) verify_epilogue_kernel(
     const int32_t *__restrict__ block_table, const int32_t *__restrict__ prefix_len,
     const int32_t *__restrict__ capacity, int32_t *__restrict__ prefix_len_out, int32_t *__restrict__ slot_map,
     int32_t *__restrict__ status, int in_place) {
-    __shared__ int32_t s_A, s_st, s_plo;
+    __shared__ int32_t s_A, s_st, s_plo, s_coop;
     __shared__ int32_t s_acc[ETV_MAX_TREE];
     __shared__ int32_t s_slot[ETV_MAX_TREE];
     const int t = threadIdx.x;
@@ -124,8 +124,8 @@ __global__ void __launch_bounds__(256) verify_epilogue_kernel(
     const int P = prefix_len[b];  // read before group 0 can have written anything (prefix_len_out is another buffer)
     posterior_for_sequence(b, t, pval, pidx, chunks, tokens, retrieve, n, T_max, L_max, W, dummy, argmax, len, best,
                            accept_len, acc_nodes, bonus, &s_A, s_acc, g == 0);
-    if (t == 0) commit_plan_for_sequence(dsc, b, block_table, P, capacity[b], n, s_acc, s_A, &s_plo, s_slot, &s_st, in_place != 0);
-    __syncthreads();
+    commit_plan_cooperative(dsc, b, block_table, P, capacity[b], n, s_acc, s_A, &s_plo, s_slot, &s_st, in_place != 0, t, 256,
+                            &s_coop);
     if (g == 0) {
         for (int i = t; i < W; i += 256) slot_map[(size_t)b * W + i] = s_slot[i];
         if (t == 0) {
