@@ -321,8 +321,11 @@ ETV_API int32_t etv_commit_accepted_kv(const etv_commit_desc *h_desc, const void
  *                                      and leave the per-tile maxima in the workspace for those calls
  *  maxval   out float [B, T_max]       the maximal logit, -inf for padded rows     nullable
  *  workspace: etv_lm_head_argmax_workspace_bytes(B, T_max, V) bytes.
- * Requires D % 128 == 0.  Built for the row counts of a verify step (B * T_max up to a few
- * hundred): up to 64 rows, and every group of 128 rows beyond that, stream the weights once (repeats come from L2).
+ * Requires D % 128 == 0.  Up to 64 rows, and every group of 128 rows beyond that, stream the weights once
+ * (repeats come from L2): the shape of a verify step, bound by the weight stream.  From 512 rows on (a batch of
+ * trees) the product is bound by the matrix cores and runs as a GEMM tiling of 256 vocabulary rows x 256 node rows
+ * per workgroup.  The result does not depend on which of the three kernels ran beyond the order of the fp32
+ * accumulation.
  * ------------------------------------------------------------------------- */
 ETV_API size_t etv_lm_head_argmax_workspace_bytes(int32_t B, int32_t T_max, int32_t V);
 

@@ -456,6 +456,151 @@ __global__ void __launch_bounds__(512, 1) lm_head_argmax_wide_kernel(LhParams p)
     }
 }
 
+// ----------------------------------------------------------------------------------------------------------------
+// Hundreds to thousands of node rows (a batch of trees): the product is no longer a weight stream but a dense
+// contraction bound by the matrix cores, and the tiling is a GEMM's.  A workgroup takes 256 vocabulary rows x 256
+// node rows; wavefront w of 8 owns 128 vocabulary rows (w % 2) x 64 node rows (w / 2) as 4 x 2 accumulators of
+// 32 x 32, so the eight products of a 16-wide contraction step need six fragments (1.3 LDS bytes per flop less
+// than the kernels above, and eight independent accumulator chains).  The contraction runs in steps of 64
+// elements: a step's weight rows (256 x 128 B) and hidden rows (256 x 128 B) are 64 KiB of LDS, two stages, filled
+// by direct-to-LDS loads one step ahead, one barrier per step (32 products per wavefront).  A 128-byte tile row
+// holds eight 16-byte chunks; chunk c of row r sits at position c ^ ((r >> 1) & 7), so the sixteen consecutive rows
+// that a 16-byte fragment read serves in one cycle fall on sixteen different bank groups.  The weights reach a
+// compute unit from L2 (the row groups of one vocabulary tile run side by side on one XCD), the hidden rows from
+// L2 and the memory-side cache.  C^T[vocab, node] as above: a node is an accumulator column, so a wavefront's
+// maximum over its 128 vocabulary rows needs one exchange between the lane halves and is exactly one per-tile
+// partial of the layout the finishing kernel (and the epilogue) reads.
+// ----------------------------------------------------------------------------------------------------------------
+constexpr int LHG_VT = 256, LHG_RT = 256;    // vocabulary rows, node rows per workgroup
+constexpr int LHG_KC = 64;                   // contraction elements per step
+constexpr int LHG_ROWB = LHG_KC * 2;         // 128 B
+constexpr int LHG_W_BYTES = LHG_VT * LHG_ROWB;            // 32 KiB
+constexpr int LHG_STAGE = LHG_W_BYTES + LHG_RT * LHG_ROWB;  // 64 KiB
+constexpr int LHG_NS = 2;
+#ifndef LHG_MIN_ROWS
+#define LHG_MIN_ROWS 512
+#endif
+
+__global__ void __launch_bounds__(512, 2) lm_head_argmax_gemm_kernel(LhParams p) {
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lh_smem;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c32 = lane & 31, hh = lane >> 5;
+    const int tiles256 = (p.tiles + 1) >> 1;
+    const int rest = blockIdx.x >> 3;
+    const int group = rest % p.groups;
+    const int tile = (rest / p.groups) * 8 + (blockIdx.x & 7);   // 256-row vocabulary tile
+    if (tile >= tiles256) return;  // uniform over the workgroup
+    const int v0 = tile * LHG_VT;
+    const int r0 = group * LHG_RT;
+    const int steps = p.D / LHG_KC;
+    const int ksteps128 = p.D / LH_KC;  // steps of the packed layout
+
+    // Loads.  A 1 KiB unit = 8 tile rows x 128 B; lane i fetches row i / 8 of the unit and the source chunk that
+    // belongs at position i % 8, i.e. chunk (i % 8) ^ ((row >> 1) & 7).  Units 0..31 are weight rows, 32..63 hidden
+    // rows; wavefront w issues units w, w + 8, w + 16, w + 24 of each: row = 8 * unit + i / 8, so
+    // (row >> 1) & 7 = (4 * (w & 1) + i / 16) & 7 for all of them.
+    const int l_row = lane >> 3;
+    const uint32_t lane_chunk = (uint32_t)((lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7));
+    const size_t row_bytes = (size_t)p.D * 2;
+    const uint8_t *wbase[4], *hbase[4];
+    uint32_t wvoff[4], hvoff[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+        const int unit = wave + 8 * u;          // rows 8 * unit .. + 7 of the 256
+        if (p.packed) {
+            // packed tiles of 128 vocabulary rows x 128 elements (32 KiB); rows past V are zero there
+            const int t128 = min(2 * tile + (unit >> 4), p.tiles - 1);
+            wbase[u] = p.weight + (size_t)t128 * ksteps128 * LH_W_BYTES + (size_t)(8 * (unit & 15)) * LH_ROWB;
+            wvoff[u] = (uint32_t)(l_row * LH_ROWB) + lane_chunk * 16;
+        } else {
+            const int vrow = min(v0 + 8 * unit + l_row, p.V - 1);
+            const int vfirst = min(v0 + 8 * unit, p.V - 1);
+            wbase[u] = p.weight + (size_t)vfirst * row_bytes;
+            wvoff[u] = (uint32_t)((size_t)(vrow - vfirst) * row_bytes) + lane_chunk * 16;
+        }
+        const int last = p.rows_total - 1;
+        const int rrow = min(r0 + 8 * unit + l_row, last);
+        const int rfirst = min(r0 + 8 * unit, last);
+        hbase[u] = p.hidden + (size_t)rfirst * row_bytes;
+        hvoff[u] = (uint32_t)((size_t)(rrow - rfirst) * row_bytes) + lane_chunk * 16;
+    }
+    auto issue = [&](int st) {
+        const uint32_t dst = smem_addr + (uint32_t)(st % LHG_NS) * LHG_STAGE + (uint32_t)wave * 1024;
+        const size_t koff = (size_t)st * LHG_ROWB;   // row-major: the next 128 B of every row
+        const size_t woff = p.packed ? (size_t)(st >> 1) * LH_W_BYTES + (size_t)(st & 1) * LHG_ROWB : koff;
+#pragma unroll
+        for (int u = 0; u < 4; u++) lh_async_load16<false>(wbase[u] + woff, wvoff[u], dst + u * 8192);
+#pragma unroll
+        for (int u = 0; u < 4; u++) lh_async_load16<false>(hbase[u] + koff, hvoff[u], dst + LHG_W_BYTES + u * 8192);
+    };
+    issue(0);
+
+    // Fragments: A = weight rows of vocabulary block vb (4 per wavefront), B = hidden rows of row block rb (2);
+    // the lane holds row c32 and the 8 contraction values at chunk 2 * kk + hh of the 64-element step.
+    const int wv = wave & 1, wr = wave >> 1;
+    const int sw = (c32 >> 1) & 7;   // (row >> 1) & 7: block bases are multiples of 32 rows
+    const uint32_t a_row = (uint32_t)((128 * wv + c32) * LHG_ROWB);
+    const uint32_t b_row = (uint32_t)(LHG_W_BYTES + (64 * wr + c32) * LHG_ROWB);
+    lh_f32x16 acc[4][2];
+#pragma unroll
+    for (int vb = 0; vb < 4; vb++)
+#pragma unroll
+        for (int rb = 0; rb < 2; rb++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) acc[vb][rb][i] = 0.f;
+
+    for (int st = 0; st < steps; st++) {
+        lh_wait_vmcnt<0>();              // this wavefront's part of step st has landed
+        __builtin_amdgcn_s_barrier();    // step st is in LDS for everyone; the stage of step st - 1 is free
+        asm volatile("" ::: "memory");
+        if (st + 1 < steps) issue(st + 1);
+        const uint8_t *stage = lh_smem + (st % LHG_NS) * LHG_STAGE;
+#pragma unroll
+        for (int kk = 0; kk < 4; kk++) {
+            const int col = ((2 * kk + hh) ^ sw) << 4;
+            lh_bf16x8 a[4], b[2];
+#pragma unroll
+            for (int vb = 0; vb < 4; vb++) a[vb] = *reinterpret_cast<const lh_bf16x8 *>(stage + a_row + vb * (32 * LHG_ROWB) + col);
+#pragma unroll
+            for (int rb = 0; rb < 2; rb++) b[rb] = *reinterpret_cast<const lh_bf16x8 *>(stage + b_row + rb * (32 * LHG_ROWB) + col);
+#pragma unroll
+            for (int vb = 0; vb < 4; vb++)
+#pragma unroll
+                for (int rb = 0; rb < 2; rb++)
+                    acc[vb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[vb], b[rb], acc[vb][rb], 0, 0, 0);
+        }
+    }
+
+    // Epilogue: per node column the maximum over the wavefront's 128 vocabulary rows, ascending (block vb, then
+    // element i of lane half hh = row 8 * (i / 4) + 4 * hh + i % 4), then over the two lane halves: one per-tile
+    // partial.  Lowest index wins among equals.
+    const int t128 = 2 * tile + wv;
+    if (t128 >= p.tiles) return;
+#pragma unroll
+    for (int rb = 0; rb < 2; rb++) {
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int vb = 0; vb < 4; vb++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const int v = v0 + 128 * wv + 32 * vb + 8 * (i >> 2) + 4 * hh + (i & 3);
+                const float x = (v < p.V) ? acc[vb][rb][i] : -INFINITY;
+                if (x > bv || (bi == 0x7fffffff && v < p.V)) { bv = x; bi = v; }
+            }
+        const float ov = __shfl_xor(bv, 32);
+        const int oi = __shfl_xor(bi, 32);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        const int row = r0 + 64 * wr + 32 * rb + c32;
+        if (hh == 0 && row < p.rows_total) {
+            const size_t o = (size_t)row * p.tiles + t128;
+            p.pval[o] = bv;
+            p.pidx[o] = bi;
+        }
+    }
+}
+
 // One wavefront per node row: reduce the per-tile partials (lowest index among equals); padded rows give -1.
 __global__ void __launch_bounds__(256) lm_head_finish_kernel(const float *__restrict__ pval,
                                                             const int32_t *__restrict__ pidx, int tiles,
@@ -546,7 +691,9 @@ extern "C" int32_t etv_lm_head_argmax(const void *hidden, const void *weight, in
     if (B == 0) return ETV_OK;
     const long rows_total = (long)B * T_max;
     const bool wide = rows_total > LH_RT;   // more than 64 rows: 128 per workgroup
-    const long rt = wide ? LHW_RT : LH_RT;
+    // from a few hundred rows on the product is bound by the matrix cores: GEMM tiling, 256 x 256 per workgroup
+    const bool gemm = rows_total >= LHG_MIN_ROWS;
+    const long rt = gemm ? LHG_RT : (wide ? LHW_RT : LH_RT);
     const long groups = (rows_total + rt - 1) / rt;
     const long tiles = ((long)V + LH_VT - 1) / LH_VT;
     if (groups > 65535 || rows_total > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;
@@ -561,17 +708,22 @@ extern "C" int32_t etv_lm_head_argmax(const void *hidden, const void *weight, in
     p.rows_total = (int)rows_total; p.T_max = T_max; p.D = D; p.V = V; p.tiles = (int)tiles; p.groups = (int)groups;
     p.packed = weight_packed ? 1 : 0;
     constexpr size_t lds = (size_t)LH_NS * LH_STAGE;
+    constexpr size_t lds_gemm = (size_t)LHG_NS * LHG_STAGE;
     static const bool lds_ok = [] {
         return hipFuncSetAttribute(reinterpret_cast<const void *>(&lm_head_argmax_kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess &&
                hipFuncSetAttribute(reinterpret_cast<const void *>(&lm_head_argmax_wide_kernel),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess &&
+               hipFuncSetAttribute(reinterpret_cast<const void *>(&lm_head_argmax_gemm_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_gemm) == hipSuccess;
     }();
     if (!lds_ok) return ETV_ERR_HIP;
     hipStream_t s = as_stream(stream);
-    const long nblocks = ((tiles + 7) / 8) * groups * 8;
+    const long vtiles = gemm ? (tiles + 1) / 2 : tiles;   // vocabulary tiles of the launch: 256 or 128 rows
+    const long nblocks = ((vtiles + 7) / 8) * groups * 8;
     if (nblocks > 0x7fffffffL) return ETV_ERR_UNSUPPORTED;
-    if (wide) hipLaunchKernelGGL(lm_head_argmax_wide_kernel, dim3((unsigned)nblocks), dim3(512), lds, s, p);
+    if (gemm) hipLaunchKernelGGL(lm_head_argmax_gemm_kernel, dim3((unsigned)nblocks), dim3(512), lds_gemm, s, p);
+    else if (wide) hipLaunchKernelGGL(lm_head_argmax_wide_kernel, dim3((unsigned)nblocks), dim3(512), lds, s, p);
     else hipLaunchKernelGGL(lm_head_argmax_kernel, dim3((unsigned)nblocks), dim3(512), lds, s, p);
     int32_t rc = check_launch();
     if (rc != ETV_OK || !argmax) return rc;  // without argmax the per-tile maxima stay in the workspace for the epilogue

@@ -84,6 +84,40 @@ def test_random_row_counts_and_vocabularies_on_the_wide_path():
         _check(h, w, n)
 
 
+def test_random_row_counts_and_vocabularies_on_the_gemm_path():
+    """From 512 node rows on the head runs as a GEMM tiling (256 vocabulary rows x 256 node rows per workgroup): row
+    counts that end inside the first, second, third or fourth 64-row block of the last row group, padded sequences,
+    vocabularies that end inside the first or the second 128-row half of a 256-row tile, one and several tiles,
+    contraction lengths of one to three packed steps."""
+    rng = np.random.default_rng(3060)
+    shapes = [(4, 128, 128, 513), (3, 200, 256, 300), (9, 100, 128, 129), (32, 33, 384, 1000), (2, 256, 128, 256),
+              (5, 103, 256, 127), (8, 65, 128, 770), (1, 600, 128, 1), (6, 97, 384, 385)]
+    for (B, T, D, V) in shapes:
+        assert B * T >= 512
+        h = _bf16(rng.standard_normal((B, T, D)))
+        w = _bf16(rng.standard_normal((V, D)) / np.sqrt(D))
+        n = [T] + [int(rng.integers(0, T + 1)) for _ in range(B - 1)]
+        _check(h, w, n)
+
+
+def test_exact_ties_on_the_gemm_path_take_the_lowest_index():
+    rng = np.random.default_rng(3110)
+    B, T, D, V = 5, 128, 128, 900
+    hb = _bf16(rng.standard_normal((B, T, D)))
+    wb = _bf16(rng.standard_normal((V, D)) / np.sqrt(D))
+    hf = synth.bf16_bits_to_f32(hb)
+    # node (2, 77): a clear winner duplicated in another 256-row tile, in the other 128-row half of its tile, in
+    # another 32-row block of its half and in the last (partial) tile
+    win = _bf16(8.0 * hf[2, 77] / float(hf[2, 77] @ hf[2, 77]))
+    for v in (300, 37, 310, 420, 899):
+        wb[v] = win
+    ref, g = _check(hb, wb, [T] * B)
+    assert g[2, 77] == 37 and ref["argmax"][2, 77] == 37
+    wb[37] = _bf16(rng.standard_normal(D) / np.sqrt(D))
+    ref, g = _check(hb, wb, [T] * B)
+    assert g[2, 77] == 300
+
+
 def test_unsupported_width_is_rejected():
     h = torch.zeros((1, 4, 64), dtype=torch.bfloat16, device="cuda")
     w = torch.zeros((10, 64), dtype=torch.bfloat16, device="cuda")
