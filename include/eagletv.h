@@ -46,6 +46,7 @@ extern "C" {
 #define ETV_ERR_UNSUPPORTED (-2)        /* dtype / head_dim / T_max / grouping outside the built kernels */
 #define ETV_ERR_WORKSPACE_TOO_SMALL (-3)
 #define ETV_ERR_HIP (-4)                /* a kernel launch failed; see etv_last_hip_error()             */
+#define ETV_ERR_UNIMPLEMENTED (-5)      /* a defined operation this library does not build (a replica of a contiguous cache) */
 
 #define ETV_F32 0
 #define ETV_BF16 1
@@ -407,7 +408,8 @@ typedef struct etv_cache_desc {
  *  free_blocks  in  int32 [n_free]            distinct blocks that no table uses (the caller's allocator)
  *  branch_table out int32 [B, N, max_blocks]
  *  block_base   out int32 [B];  n_taken out int32 [1];  status out int32 [B]
- * All device pointers.  Requires block_size > 0 and d * elem_bytes % 16 == 0. */
+ * All device pointers.  Requires d * elem_bytes % 16 == 0 and a paged cache: block_size == 0 (a contiguous
+ * cache, whose replica would be the paper's deep copy) returns ETV_ERR_UNIMPLEMENTED. */
 ETV_API int32_t etv_replicate_branches(const etv_cache_desc *h_desc, void *k_cache, void *v_cache,
                                const int32_t *block_table, const int32_t *prefix_len, const int32_t *tail_len,
                                int32_t N, const int32_t *free_blocks, int32_t n_free, int32_t *branch_table,

@@ -16,6 +16,7 @@ extern "C" const char *etv_status_string(int32_t status) {
         case ETV_ERR_UNSUPPORTED: return "unsupported shape or dtype";
         case ETV_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case ETV_ERR_HIP: return "HIP launch error";
+        case ETV_ERR_UNIMPLEMENTED: return "not implemented";
         default: return "unknown status";
     }
 }

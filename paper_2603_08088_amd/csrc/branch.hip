@@ -320,7 +320,7 @@ static int32_t check_cache_desc(const etv_cache_desc *h, bool need_paged) {
     if (h->B < 0 || h->Hkv < 1 || h->d < 1 || h->n_layers < 1 || h->block_size < 0) return ETV_ERR_INVALID_ARG;
     if (h->elem_bytes != 2 && h->elem_bytes != 4) return ETV_ERR_UNSUPPORTED;
     if (((size_t)h->d * h->elem_bytes) % 16 != 0) return ETV_ERR_UNSUPPORTED;
-    if (need_paged && h->block_size == 0) return ETV_ERR_UNSUPPORTED;
+    if (need_paged && h->block_size == 0) return ETV_ERR_UNIMPLEMENTED;  // replication of a contiguous cache: not built
     if (h->block_size > 0 && (h->max_blocks < 1 || h->num_blocks < 1)) return ETV_ERR_INVALID_ARG;
     if (h->block_size == 0 && h->P_cap < 1) return ETV_ERR_INVALID_ARG;
     if (h->cache_layer_stride < 0 || ((size_t)h->cache_layer_stride * h->elem_bytes) % 16 != 0) return ETV_ERR_INVALID_ARG;

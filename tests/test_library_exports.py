@@ -40,6 +40,12 @@ def test_host_only_calls_need_no_gpu():
     lib = api.lib()
     assert b"gfx950" in lib.etv_version()
     assert lib.etv_status_string(0) == b"ok" and lib.etv_status_string(-3) == b"workspace too small"
+    assert lib.etv_status_string(-5) == b"not implemented"
+    # a replica of a contiguous cache is a defined operation that is not built: refused on the host, before any pointer is used
+    cd = api.CacheDesc(B=1, Hkv=2, d=64, elem_bytes=2, n_layers=1, block_size=0, max_blocks=0, num_blocks=0, P_cap=64,
+                       reserved=0, cache_layer_stride=64 * 2 * 64)
+    assert lib.etv_replicate_branches(ctypes.byref(cd), None, None, None, None, None, 1, None, 0, None, None, None, None,
+                                      None) == -5
     dsc = api.AttnDesc(B=1, T_max=60, Hq=32, Hkv=8, d=128, dtype=api.BF16, block_size=0, max_blocks=0, num_blocks=0,
                        P_cap=2100, P_max=2048, scale=0.0, kv_split=0, flags=0)
     ws = api.tree_verify_attention_workspace_bytes(dsc)
