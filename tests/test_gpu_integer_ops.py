@@ -478,3 +478,47 @@ def test_fused_epilogue_refuses_an_aliased_prefix_length_output():
     with pytest.raises(api.EtvError):
         api.verify_epilogue(d.logits, d.tokens, d.retrieve, d.n_nodes, d.kt[None], d.vt[None], kc, vc, d.prefix_len,
                             d.capacity, commit_out=dict(prefix_len_out=d.prefix_len))
+
+
+@pytest.mark.parametrize("in_place", [False, True])
+def test_fused_epilogue_on_a_fully_accepted_256_node_chain_and_on_a_batch_of_600(in_place):
+    """The extremes of the one-launch epilogue: an accepted path of 256 rows (every thread of the plan has a
+    position, the row copy runs over sixteen batches) over three layers, and 600 sequences (one layer group per
+    sequence, more acceptance workgroups than compute units)."""
+    rng = np.random.default_rng(93 + in_place)
+    T, L = 256, 3
+    wl = synth.assemble("chain256", rng, [synth.tree_chain(T)], [77], Hq=2, Hkv=2, d=64, dtype="bf16", V=300, W=T,
+                        paged=True, T_max=T, spare_blocks=3, tail_room=T, with_logits=False)
+    g = np.zeros((1, T), dtype=np.int32)
+    g[0, :T - 1] = wl.tokens[0, 1:]                       # every node's choice is its child's token
+    g[0, T - 1] = 11
+    kc = np.stack([synth._values(rng, wl.k_cache.shape, "bf16") for _ in range(L)])
+    vc = np.stack([synth._values(rng, wl.v_cache.shape, "bf16") for _ in range(L)])
+    kt = np.stack([synth._values(rng, wl.kt.shape, "bf16") for _ in range(L)])
+    vt = np.stack([synth._values(rng, wl.vt.shape, "bf16") for _ in range(L)])
+    d = DevWorkload(wl)
+    rp = oracle.evaluate_posterior(synth_logits_from(g, 300), wl.tokens, wl.retrieve, wl.n_nodes)
+    assert rp["accept_len"].tolist() == [T - 1] and rp["bonus"].tolist() == [11]
+    okc, ovc = kc.copy(), vc.copy()
+    rc = oracle.commit_accepted_kv(None if in_place else kt, None if in_place else vt, okc, ovc, wl.prefix_len,
+                                   wl.capacity, wl.n_nodes, rp["acc_nodes"], rp["accept_len"],
+                                   block_table=wl.block_table, T_max=T)
+    assert rc["status"].tolist() == [0] and int(rc["prefix_len_out"][0]) == 77 + T
+    dkc, dvc = to_dev(kc), to_dev(vc)
+    _, p, c = api.verify_epilogue(None, d.tokens, d.retrieve, d.n_nodes, None if in_place else to_dev(kt),
+                                  None if in_place else to_dev(vt), dkc, dvc, d.prefix_len, d.capacity,
+                                  block_table=d.block_table, post_out=dict(argmax=to_dev(g)))
+    torch.cuda.synchronize()
+    for key in rp:
+        assert np.array_equal(bits_of(p[key]), rp[key]), key
+    for key in rc:
+        assert np.array_equal(bits_of(c[key]), rc[key]), key
+    assert np.array_equal(bits_of(dkc), okc) and np.array_equal(bits_of(dvc), ovc)
+    if in_place:
+        return
+    # 600 short sequences with ragged accept lengths, two layers
+    B = 600
+    parents = [random_tree(rng, 9) for _ in range(B)]
+    wl = synth.assemble("many", rng, parents, [int(x) for x in rng.integers(0, 40, size=B)], Hq=2, Hkv=2, d=64,
+                        dtype="bf16", V=64, W=9, paged=True, T_max=9, spare_blocks=3)
+    _epilogue_case(wl, L=2)

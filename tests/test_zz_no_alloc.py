@@ -66,3 +66,35 @@ def test_static_workspace_call_refuses_shapes_beyond_its_array():
     assert e.value.rc == -3
     torch.cuda.synchronize()
     assert torch.all(out == 7.0)                           # nothing was launched
+
+
+def test_static_workspace_call_inside_a_replayed_hip_graph():
+    """What the entry point is for: captured once, replayed several times with new inputs in the same buffers and
+    eager work in between; every replay must give the bits of an eager call with a workspace on the same inputs."""
+    wl = _workload(4103, 2, 40, [900, 333], [40, 17], True)
+    d = DevWorkload(wl)
+    m = api.build_tree_mask(d.parent, d.n_nodes)
+    out = torch.empty_like(d.q)
+    lse = torch.empty((wl.B, wl.Hq, wl.T_max), dtype=torch.float32, device=d.q.device)
+
+    def call():
+        api.tree_verify_attention_static(d.q, d.k_cache, d.v_cache, d.prefix_len, d.kt, d.vt, m["bitmask"], d.n_nodes,
+                                         out, lse, P_max=d.P_max, block_table=d.block_table, kv_split=128)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()                                            # first call on the device outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    for rep in range(4):
+        d.q.copy_(torch.randn(d.q.shape, generator=gen, device="cuda").to(torch.bfloat16))   # eager work between replays
+        d.kt.copy_(torch.randn(d.kt.shape, generator=gen, device="cuda").to(torch.bfloat16))
+        out.fill_(7.0)
+        graph.replay()
+        ref_out, ref_lse = gpu_attention(d, m["bitmask"], kv_split=128)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref_out) and torch.equal(lse, ref_lse), rep
