@@ -253,7 +253,8 @@ def run_probes(torch):
 
 
 class AttnOnly:
-    """Attention launches of one configuration over enough layers of cache that K/V streams from HBM."""
+    """Attention launches of one configuration over enough layers of cache (at least eight, at least 640 MB) that
+    K/V streams from HBM."""
 
     def __init__(self, name, torch, api):
         from paper_2603_08088_amd.devio import to_dev
@@ -267,7 +268,9 @@ class AttnOnly:
         per_layer = 2 * 2
         for x in cshape:
             per_layer *= x
-        self.layers = max(2, -(-640 * 2 ** 20 // per_layer))
+        # at least eight launches per sample: a graph replay costs several microseconds of its own, which two
+        # launches of 90 us would each carry half of
+        self.layers = max(8, -(-640 * 2 ** 20 // per_layer))
         L = self.layers
         self.q = torch.randn((L, B, T, Hq, d), generator=gen, device=dev).to(bf)
         self.kt = torch.randn((L, B, T, Hkv, d), generator=gen, device=dev).to(bf)
