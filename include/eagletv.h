@@ -323,7 +323,7 @@ ETV_API int32_t etv_commit_accepted_kv(const etv_commit_desc *h_desc, const void
  *  maxval   out float [B, T_max]       the maximal logit, -inf for padded rows     nullable
  *  workspace: etv_lm_head_argmax_workspace_bytes(B, T_max, V) bytes.
  * Requires D % 128 == 0.  Up to 64 rows, and every group of 128 rows beyond that, stream the weights once
- * (repeats come from L2): the shape of a verify step, bound by the weight stream.  From 512 rows on (a batch of
+ * (repeats come from L2): the shape of a verify step, bound by the weight stream.  Beyond 256 rows (a batch of
  * trees) the product is bound by the matrix cores and runs as a GEMM tiling of 256 vocabulary rows x 256 node rows
  * per workgroup.  The result does not depend on which of the three kernels ran beyond the order of the fp32
  * accumulation.

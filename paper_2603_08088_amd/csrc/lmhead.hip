@@ -457,7 +457,7 @@ __global__ void __launch_bounds__(512, 1) lm_head_argmax_wide_kernel(LhParams p)
 }
 
 // ----------------------------------------------------------------------------------------------------------------
-// Hundreds to thousands of node rows (a batch of trees): the product is no longer a weight stream but a dense
+// More than 256 node rows (a batch of trees): the product is no longer a weight stream but a dense
 // contraction bound by the matrix cores, and the tiling is a GEMM's.  A workgroup takes 256 vocabulary rows x 256
 // node rows; wavefront w of 8 owns 128 vocabulary rows (w % 2) x 64 node rows (w / 2) as 4 x 2 accumulators of
 // 32 x 32, so the eight products of a 16-wide contraction step need six fragments (1.3 LDS bytes per flop less
@@ -477,9 +477,7 @@ constexpr int LHG_ROWB = LHG_KC * 2;         // 128 B
 constexpr int LHG_W_BYTES = LHG_VT * LHG_ROWB;            // 32 KiB
 constexpr int LHG_STAGE = LHG_W_BYTES + LHG_RT * LHG_ROWB;  // 64 KiB
 constexpr int LHG_NS = 2;
-#ifndef LHG_MIN_ROWS
-#define LHG_MIN_ROWS 512
-#endif
+constexpr int LHG_MIN_ROWS = 257;   // measured: from 257 rows on this tiling beats the 128-row groups (288 rows: 129 vs 143 us)
 
 __global__ void __launch_bounds__(512, 2) lm_head_argmax_gemm_kernel(LhParams p) {
     const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lh_smem;

@@ -23,7 +23,7 @@ TOL = {"f32": 1e-5, "bf16": 2e-2}
 REL_TOL = {"f32": 1e-5, "bf16": 2e-2}   # max of |err| / (|ref| + rms(ref))
 
 # worst observed errors per test, written as JSON to $ETV_ERROR_REPORT when that is set (a record for the
-# tolerance table of the design notes; the assertions do not depend on it)
+# record of the tolerances actually needed; the assertions do not depend on it)
 _WORST = {}
 
 

@@ -85,15 +85,16 @@ def test_random_row_counts_and_vocabularies_on_the_wide_path():
 
 
 def test_random_row_counts_and_vocabularies_on_the_gemm_path():
-    """From 512 node rows on the head runs as a GEMM tiling (256 vocabulary rows x 256 node rows per workgroup): row
+    """Beyond 256 node rows the head runs as a GEMM tiling (256 vocabulary rows x 256 node rows per workgroup): row
     counts that end inside the first, second, third or fourth 64-row block of the last row group, padded sequences,
     vocabularies that end inside the first or the second 128-row half of a 256-row tile, one and several tiles,
     contraction lengths of one to three packed steps."""
     rng = np.random.default_rng(3060)
     shapes = [(4, 128, 128, 513), (3, 200, 256, 300), (9, 100, 128, 129), (32, 33, 384, 1000), (2, 256, 128, 256),
-              (5, 103, 256, 127), (8, 65, 128, 770), (1, 600, 128, 1), (6, 97, 384, 385)]
+              (5, 103, 256, 127), (8, 65, 128, 770), (1, 600, 128, 1), (6, 97, 384, 385), (1, 257, 128, 300),
+              (8, 60, 256, 641), (3, 111, 128, 64)]
     for (B, T, D, V) in shapes:
-        assert B * T >= 512
+        assert B * T > 256
         h = _bf16(rng.standard_normal((B, T, D)))
         w = _bf16(rng.standard_normal((V, D)) / np.sqrt(D))
         n = [T] + [int(rng.integers(0, T + 1)) for _ in range(B - 1)]
