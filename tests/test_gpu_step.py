@@ -112,3 +112,90 @@ def test_full_step_config2_eager_and_graph(paged, fused):
         torch.cuda.synchronize()
         g.replay()
         check(dkc2, dvc2, f"graph replay {rep}")
+
+
+def test_full_step_headline_sweep_cell_as_a_replayed_graph():
+    """The benchmark's default workload at full size (B = 32, P = 4096 paged, T = 128, depth 10, V = 32000; two layers
+    instead of 32) in the launch configuration it times: tree tensors, attention per layer, fused epilogue, replayed as
+    a HIP graph.  Every integer output and every cache byte against the oracle over the full batch; attention against
+    the oracle on two seeded sequences per layer (all heads and rows; the full sweep of cells is in
+    test_gpu_attention.py)."""
+    L = 2
+    wl = synth.config5(128, 10)
+    rng = np.random.default_rng(98)
+    q = np.stack([wl.q] + [synth._values(rng, wl.q.shape, "bf16") for _ in range(L - 1)])
+    kt = np.stack([wl.kt] + [synth._values(rng, wl.kt.shape, "bf16") for _ in range(L - 1)])
+    vt = np.stack([wl.vt] + [synth._values(rng, wl.vt.shape, "bf16") for _ in range(L - 1)])
+    kc = np.stack([wl.k_cache] + [synth._values(rng, wl.k_cache.shape, "bf16") for _ in range(L - 1)])
+    vc = np.stack([wl.v_cache] + [synth._values(rng, wl.v_cache.shape, "bf16") for _ in range(L - 1)])
+    B, T, W, L_max = wl.B, wl.T_max, wl.W, wl.retrieve.shape[1]
+    # oracle, integer path over the full batch
+    rm = oracle.build_tree_mask(wl.parent, wl.n_nodes)
+    rt = oracle.tensorize_tree(wl.parent, wl.n_nodes, wl.prefix_len, L_max, W)
+    assert np.array_equal(rt["retrieve"], wl.retrieve) and (wl.retrieve < 0).mean() >= 0.5   # padding-heavy, as specified
+    rg = oracle.safe_gather_paths(wl.retrieve, wl.n_nodes, T, 0, wl.tokens.reshape(B, T, 1))
+    rp = oracle.evaluate_posterior(wl.logits, wl.tokens, wl.retrieve, wl.n_nodes)
+    assert rp["accept_len"].tolist() == [a for _, a in wl.planted]
+    rkc, rvc = kc.copy(), vc.copy()
+    rc = oracle.commit_accepted_kv(kt, vt, rkc, rvc, wl.prefix_len, wl.capacity, wl.n_nodes, rp["acc_nodes"],
+                                   rp["accept_len"], block_table=wl.block_table)
+    assert np.all(rc["status"] == 0)
+
+    d = DevWorkload(wl)
+    dq, dkt, dvt, dkc, dvc = to_dev(q), to_dev(kt), to_dev(vt), to_dev(kc), to_dev(vc)
+    out = torch.empty_like(dq)
+    desc = api.attn_desc(dq[0], dkt[0], dkc[0], d.block_table, d.P_max)
+    plan = api.tree_verify_attention_plan(desc)
+    assert plan["mfma"] == 1 and plan["wavefronts"] == 8 and plan["n_splits"] == 1      # the shape bench.py reports
+    ws = torch.empty(max(256, api.tree_verify_attention_workspace_bytes(desc)), dtype=torch.uint8, device="cuda")
+    pws = torch.empty(max(256, api.evaluate_posterior_workspace_bytes(B, T, wl.V)), dtype=torch.uint8, device="cuda")
+    holder = {}
+
+    def step():
+        m = api.tensorize_tree(d.parent, d.n_nodes, d.prefix_len, L_max, W, out=holder.get("m"))
+        holder["m"] = m
+        for l in range(L):
+            api.tree_verify_attention(dq[l], dkc[l], dvc[l], d.prefix_len, dkt[l], dvt[l], m["bitmask"], d.n_nodes,
+                                      P_max=d.P_max, block_table=d.block_table, out=out[l], want_lse=False,
+                                      workspace=ws, desc=desc)
+        holder["e"] = api.verify_epilogue(d.logits, d.tokens, m["retrieve"], d.n_nodes, dkt, dvt, dkc, dvc, d.prefix_len,
+                                          d.capacity, block_table=d.block_table, src=d.tokens.reshape(B, T, 1),
+                                          workspace=pws, gather_out=holder.get("g"), post_out=holder.get("p"),
+                                          commit_out=holder.get("c"))
+        holder["g"], holder["p"], holder["c"] = holder["e"]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                             # allocates the outputs once, outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    seqs = sorted(int(x) for x in np.random.default_rng(97).choice(B, size=2, replace=False))
+    for rep in range(2):
+        out.zero_(); holder["p"]["accept_len"].fill_(-7); holder["c"]["slot_map"].fill_(-7)
+        dkc.copy_(to_dev(kc)); dvc.copy_(to_dev(vc))       # eager work between replays: the caches are committed into
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        m, g, p, c = holder["m"], holder["g"], holder["p"], holder["c"]
+        assert np.array_equal(bits_of(m["dense"]), rm["dense"]) and np.array_equal(bits_of(m["status"]), rm["status"])
+        for key in ("depth", "position_ids", "retrieve", "n_paths"):
+            assert np.array_equal(bits_of(m[key]), rt[key]), (rep, key)
+        for key in ("safe", "pvalid", "gathered"):
+            assert np.array_equal(bits_of(g[key]), rg[key]), (rep, key)
+        for key in rp:
+            assert np.array_equal(bits_of(p[key]), rp[key]), (rep, key)
+        for key in rc:
+            assert np.array_equal(bits_of(c[key]), rc[key]), (rep, key)
+        assert np.array_equal(bits_of(dkc), rkc) and np.array_equal(bits_of(dvc), rvc), rep
+        for l in range(L):
+            for b in seqs:
+                sl = slice(b, b + 1)
+                ref, _ = oracle.tree_verify_attention(q[l][sl], kc[l], vc[l], wl.prefix_len[sl], kt[l][sl], vt[l][sl],
+                                                      rm["dense"][sl], wl.n_nodes[sl], dtype="bf16",
+                                                      block_table=wl.block_table[sl], want_lse=False)
+                err, rel, pz = attention_errors(out[l][sl], ref, wl.n_nodes[sl])
+                assert pz and err <= 2e-2 and rel <= 2e-2, (rep, l, b, err, rel)
