@@ -6,7 +6,8 @@ One step = one pass of the whole verification path over one batch of synthetic i
   evaluate_posterior -> commit_accepted_kv over all layers (one launch),
 with every input already resident in HBM.  The step is captured once into a HIP graph per cache
 set and replayed; cache sets are rotated so that consecutive steps stream K/V from HBM, not from
-the 256 MB memory-side cache.  Prints ONE JSON line (metric: tree-verify tokens/s).
+the 256 MB memory-side cache.  Prints ONE compact JSON line on stdout (metric: tree-verify tokens/s); --report FILE
+writes the full report (plans, traffic, sample descriptions, every figure unrounded) as well ("-": to stderr).
 
 The default workload is the largest single-GPU configuration: the T = 128, depth 10 cell of the budget sweep
 (B = 32 sequences, 4096-token paged prefixes, 32 layers).  Beside the headline the line carries
@@ -55,6 +56,7 @@ def parse_args():
     ap.add_argument("--no-configs", action="store_true", help="skip the per-configuration table of attention launches")
     ap.add_argument("--samples", type=int, default=50, help="event-timed samples per figure (at least 50)")
     ap.add_argument("--no-probes", action="store_true", help="skip the stream-read and MFMA probes")
+    ap.add_argument("--report", default="", help="also write the full report (JSON) to this file; '-' = one line on stderr")
     ap.add_argument("--sets", type=int, default=0, help="cache sets to rotate over (0 = enough to exceed 640 MB)")
     return ap.parse_args()
 
@@ -609,7 +611,60 @@ def main():
         "roofline": roof, "cpu_baseline": cpu, "timing": timing, "configs": configs, "lm_head_argmax": head,
         "branch_cache": branch,
     }
-    print(json.dumps(line))
+    # The full report (every figure, the plans, the sample descriptions) goes to the file named by --report ("-":
+    # stderr); stdout carries ONE compact JSON line with the same keys: numbers rounded to four significant digits, the
+    # per-configuration table as rows of [median us, min us, HBM fraction, MFMA fraction, counter traffic /
+    # algorithmic bytes], so that the line stays a few KB for whatever reads the tail of the output.
+    if a.report == "-":
+        print("bench report: " + json.dumps(line), file=sys.stderr, flush=True)
+    elif a.report:
+        with open(a.report, "w") as f:
+            json.dump(line, f, indent=1)
+    print(json.dumps(compact(line)), flush=True)
+
+
+def compact(line):
+    def r4(x):
+        if isinstance(x, float):
+            return float(f"{x:.4g}")
+        if isinstance(x, dict):
+            return {k: r4(v) for k, v in x.items()}
+        if isinstance(x, list):
+            return [r4(v) for v in x]
+        return x
+    out = {k: line[k] for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better",
+                                "scaling", "vs_baseline", "dtype", "data")}
+    out["config"] = {k: line["config"][k] for k in ("workload", "layers", "tokens_per_step", "launch")}
+    roof = dict(line["roofline"])
+    roof.pop("plan", None)
+    m = roof.get("measured_mfma_tflops")
+    if m:
+        roof["measured_mfma_tflops"] = {k: m[k] for k in ("first_launch", "sustained")}
+    roof["kernel"] = "tree_verify_attention (attn_mfma_kernel)"
+    out["roofline"] = r4(roof)
+    cpu = line["cpu_baseline"]
+    if cpu:
+        cpu = dict(cpu)
+        cpu["sample"] = cpu["sample"][:160]
+        cpu.pop("seconds", None)
+    out["cpu_baseline"] = r4(cpu)
+    out["timing_us_median_min"] = {k: [r4(v["median_us"]), r4(v["min_us"])] for k, v in line["timing"].items()}
+    out["timing_samples"] = min(v["samples"] for v in line["timing"].values())
+    if line["configs"]:
+        out["configs_columns"] = ["us_per_launch_median", "us_per_launch_min", "hbm_frac", "mfma_frac",
+                                  "traffic_over_algorithmic_bytes"]
+        out["configs"] = {k: [r4(v["us_per_launch_median"]), r4(v["us_per_launch_min"]), r4(v["hbm_frac"]),
+                              r4(v["mfma_frac"]),
+                              r4(v["traffic"] / v["algorithmic_bytes"]) if v["traffic"] else None]
+                          for k, v in line["configs"].items()}
+    h = line["lm_head_argmax"]
+    if h:
+        out["lm_head_argmax"] = r4({k: h[k] for k in ("rows", "us_per_call", "mfma_tflops", "hbm_gbs")})
+    b = line["branch_cache"]
+    if b:
+        out["branch_cache"] = r4({k: b[k] for k in ("replicate_us", "commit_path_indices_fast_us",
+                                                    "commit_path_indices_full_reorder_us", "full_reorder_hbm_gbs")})
+    return out
 
 
 if __name__ == "__main__":
