@@ -326,6 +326,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     return __builtin_bit_cast(uint32_t, r);
 }
 
+// acc + the two bf16 values of a packed pair, in fp32: one instruction for two probabilities.  The row sum is
+// taken over the probabilities as rounded to bf16, i.e. over exactly the weights the PV product uses.
+__device__ __forceinline__ float pair_sum(uint32_t packed, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed), __builtin_bit_cast(bf16x2, 0x3f803f80u),
+                                           acc, false);
+}
+
 // 16 bytes per lane from global memory straight into LDS at (lds_addr + 16 * lane); asynchronous.
 __device__ __forceinline__ void async_load16(const void *gptr, uint32_t lds_addr) {
     // lds_addr is the same in every lane; readfirstlane says so to the compiler whatever it concluded about the loop
@@ -548,7 +555,7 @@ __device__ __forceinline__ void qk_softmax(const TileView &tv, const uint8_t *lk
             for (int i = 0; i < 16; i++) oacc[db][i] *= alpha;
     }
     const float neg_m = (MASKED && m_run == -INFINITY) ? 0.f : -m_run;
-    float psum = 0.f;
+    float psum = 0.f, psum2 = 0.f;  // two chains
     uint32_t pk0[8], pk1[8];
 #pragma unroll
     for (int i = 0; i < 16; i += 2) {
@@ -556,15 +563,16 @@ __device__ __forceinline__ void qk_softmax(const TileView &tv, const uint8_t *lk
         const float a1 = __builtin_amdgcn_exp2f(fmaf(s0[i + 1], scale_log2, neg_m));
         const float b0 = __builtin_amdgcn_exp2f(fmaf(s1[i], scale_log2, neg_m));
         const float b1 = __builtin_amdgcn_exp2f(fmaf(s1[i + 1], scale_log2, neg_m));
-        psum += (a0 + a1) + (b0 + b1);
         pk0[i >> 1] = pack_bf16x2(a0, a1);
         pk1[i >> 1] = pack_bf16x2(b0, b1);
+        psum = pair_sum(pk0[i >> 1], psum);
+        psum2 = pair_sum(pk1[i >> 1], psum2);
     }
     const uint4 l0 = {pk0[0], pk0[1], pk0[2], pk0[3]}, h0 = {pk0[4], pk0[5], pk0[6], pk0[7]};
     const uint4 l1 = {pk1[0], pk1[1], pk1[2], pk1[3]}, h1 = {pk1[4], pk1[5], pk1[6], pk1[7]};
     pf[0][0] = __builtin_bit_cast(bf16x8, l0); pf[0][1] = __builtin_bit_cast(bf16x8, h0);
     pf[1][0] = __builtin_bit_cast(bf16x8, l1); pf[1][1] = __builtin_bit_cast(bf16x8, h1);
-    l_run += psum;
+    l_run += psum + psum2;
 }
 
 // Second half: O^T += V^T P^T over the 64 keys of the V tile at lv; four independent accumulator chains.
@@ -646,8 +654,8 @@ __device__ __forceinline__ void qk_softmax_half(const TileView &tv, const uint8_
     for (int i = 0; i < 16; i += 2) {
         const float a0 = __builtin_amdgcn_exp2f(fmaf(s0[i], scale_log2, neg_m));
         const float a1 = __builtin_amdgcn_exp2f(fmaf(s0[i + 1], scale_log2, neg_m));
-        psum += a0 + a1;
         pk[i >> 1] = pack_bf16x2(a0, a1);
+        psum = pair_sum(pk[i >> 1], psum);
     }
     const uint4 l0 = {pk[0], pk[1], pk[2], pk[3]}, h0 = {pk[4], pk[5], pk[6], pk[7]};
     pf[0] = __builtin_bit_cast(bf16x8, l0);
