@@ -170,6 +170,8 @@ typedef struct etv_attn_desc {
 #define ETV_ATTN_FLAG_KEY_HALVES 8 /* two wavefronts per 32-row chunk wherever the tree is small enough (tuning) */
 
 #define ETV_ATTN_FLAG_LARGE_WG 16 /* 8-wavefront workgroups wherever the tree has enough rows for them (tuning) */
+#define ETV_ATTN_FLAG_UNIFORM_SPLITS 32 /* one split size for the whole batch, also where the splits could follow the
+                                           sequences' lengths (tuning) */
 
 ETV_API size_t etv_tree_verify_attention_workspace_bytes(const etv_attn_desc *h_desc);
 
@@ -186,7 +188,9 @@ typedef struct etv_attn_plan {
     int32_t row_groups;  /* workgroups per (split, KV head, sequence) */
     int32_t kv_split;    /* prefix keys per split (multiple of 64) */
     int32_t n_splits;    /* splits the launch provides; more than 1 means partials + the combine launch */
-    int32_t reserved;
+    int32_t balanced_splits; /* 1: the launch's B * n_splits split slots are shared out among the sequences by their
+                                lengths (on the device): sequence b cuts its prefix into as many equal parts as its
+                                share; kv_split is then the size for a sequence of P_max keys */
     int64_t workgroups;  /* grid size of the partial kernel */
 } etv_attn_plan;
 

@@ -28,6 +28,7 @@ ATTN_FLAG_SMALL_WG = 2
 ATTN_FLAG_WHOLE_TILE = 4
 ATTN_FLAG_KEY_HALVES = 8
 ATTN_FLAG_LARGE_WG = 16
+ATTN_FLAG_UNIFORM_SPLITS = 32
 MAX_TREE, ATTN_MAX_TREE = 256, 256
 ATTN_STATIC_WORKSPACE_BYTES = 64 << 20
 
@@ -48,7 +49,7 @@ class AttnDesc(C.Structure):
 
 class AttnPlan(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("mfma", "wavefronts", "key_halves", "ring_stages", "row_groups", "kv_split",
-                                         "n_splits", "reserved")] + [("workgroups", C.c_int64)]
+                                         "n_splits", "balanced_splits")] + [("workgroups", C.c_int64)]
 
 
 class CommitDesc(C.Structure):

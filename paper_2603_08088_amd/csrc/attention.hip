@@ -31,14 +31,20 @@ struct AttnParams {
     int pairs;   // mfma kernel: 32-row chunks of the packed query rows of a KV head
     int wgp;     // mfma kernel: workgroups per (b, kv head, split) = ceil(pairs / 4)
     float scale_log2;
+    // mfma kernel, batches of 2 .. 64 sequences with splits: the B * nsplit split slots are shared out among the
+    // sequences by their lengths (on the device, where the lengths are), slot-major partials
+    //   part_o [B * nsplit][Hq][T_max][d]; split_tab[b] = (first slot, splits in use) for the combine kernel
+    int balanced;
+    int2 *split_tab;
 };
 
 constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ int seq_prefix_len(const AttnParams &p, int b) { return clampi(p.prefix_len[b], 0, p.P_max); }
 __device__ __forceinline__ int seq_nsplit(const AttnParams &p, int P) { return max(1, (P + p.chunk - 1) / p.chunk); }
-__device__ __forceinline__ size_t part_row(const AttnParams &p, int b, int s, int h, int k) {
-    return (((size_t)b * p.nsplit + s) * p.Hq + h) * p.T_max + k;
+// partial row of split slot `slot` (= b * nsplit + s where every sequence owns nsplit slots)
+__device__ __forceinline__ size_t part_row(const AttnParams &p, int slot, int h, int k) {
+    return ((size_t)slot * p.Hq + h) * p.T_max + k;
 }
 
 // element offset of prefix row `key` of KV head kvh (contiguous or paged cache)
@@ -62,6 +68,68 @@ __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
     return v;
+}
+
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+__device__ __forceinline__ int wave_max_i(int v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = max(v, __shfl_xor(v, off));
+    return v;
+}
+
+// Balanced splits.  With one split size for the whole batch a ragged batch leaves the split slots of its short
+// sequences empty while the workgroups of its longest sequence decide the launch time.  Here the launch's
+// S = B * nsplit slots are shared out by length: L = the smallest tile count with sum_b max(1, ceil(tiles_b / L))
+// <= S (tiles_b: 64-key tiles of the prefix and of the tree), sequence b gets ceil(tiles_b / L) consecutive slots
+// and cuts its prefix evenly over them; its last split in use also takes the tree.  Every wavefront works this
+// out for itself, lane i holding sequence i (B <= 64): integer arithmetic only, so all of them agree.
+struct SplitShare {
+    int b, j, nvalid, start, tps, P_raw, n_raw;  // sequence, split within it, splits in use, first slot, tiles per split
+    bool live;
+};
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ inline SplitShare balanced_share(const AttnParams &p, int x, int lane) {
+    const bool has = lane < p.B;
+    const int P_raw = has ? p.prefix_len[lane] : 0, n_raw = has ? p.n_nodes[lane] : 0;
+    const int P = clampi(P_raw, 0, p.P_max), n = clampi(n_raw, 0, p.T_max);
+    const int pt = (P + 63) >> 6;
+    const int tt = pt + ((n + 63) >> 6);
+    const int S = p.B * p.nsplit;
+    const int total = uni(wave_sum_i(tt));
+    int hi = max(1, uni(wave_max_i(tt)));                                   // one slot per sequence always fits
+    if (S > p.B) hi = min(hi, max(1, (total + (S - p.B) - 1) / (S - p.B)));  // sum (tiles_b / L + 1) <= S
+    int lo = min(hi, max(1, (total + S - 1) / S));
+    while (lo < hi) {  // sum_b max(1, ceil(tiles_b / L)) falls as L grows
+        const int mid = (lo + hi) >> 1;
+        const int cnt = uni(wave_sum_i(has ? max(1, (tt + mid - 1) / mid) : 0));
+        if (cnt <= S) hi = mid;
+        else lo = mid + 1;
+    }
+    const int ns = has ? max(1, (tt + lo - 1) / lo) : 0;  // slots of the lane's sequence
+    const int tps = max(1, (tt + max(ns, 1) - 1) / max(ns, 1));
+    const int nv = max(1, (pt + tps - 1) / tps);          // of them in use: those that hold prefix keys
+    int incl = ns;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int v = __shfl_up(incl, off);
+        if (lane >= off) incl += v;
+    }
+    const int start = incl - ns;  // strictly increasing over the sequences
+    const int owner = uni(__popcll(__ballot(has && start <= x)) - 1);
+    SplitShare r;
+    r.b = owner;
+    r.start = uni(__shfl(start, owner));
+    r.j = x - r.start;
+    r.nvalid = uni(__shfl(nv, owner));
+    r.tps = uni(__shfl(tps, owner));
+    r.P_raw = uni(__shfl(P_raw, owner));
+    r.n_raw = uni(__shfl(n_raw, owner));
+    r.live = owner >= 0 && r.j < r.nvalid;
+    return r;
 }
 
 template <typename T>
@@ -194,7 +262,7 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(AttnParams p) {
         for (int i = 0; i < DPL; i++) store_elem<T>(out, orow + lane + 64 * i, o[i] * inv);
         if (p.lse && lane == 0) p.lse[((size_t)b * p.Hq + h) * p.T_max + k] = (m + log2f(l)) * kLn2;
     } else {
-        const size_t pr = part_row(p, b, s, h, k);
+        const size_t pr = part_row(p, b * p.nsplit + s, h, k);
 #pragma unroll
         for (int i = 0; i < DPL; i++) p.part_o[pr * D + lane + 64 * i] = o[i];
         if (lane == 0) {
@@ -208,10 +276,11 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(AttnParams p) {
 // Combine: grid (T_max, Hq, B), D threads.  out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
 // ----------------------------------------------------------------------------------------------
 // WPR wavefronts per query row (b, k, h), 4 / WPR rows per workgroup; a lane owns D / (64 * WPR) consecutive output
-// elements (two wavefronts per row for small launches, where the latency of a row's chain is what counts).
-// One pass over the splits in batches of eight (only splits that exist are read; a batch's loads are all in flight
-// together), with a running (M, L, acc) that is rescaled when a later batch raises the maximum.
-template <typename T, int D, int WPR>
+// elements (two wavefronts per row for small launches, where the latency of a row's chain is what counts).  Two
+// trips to memory: the sequence's sizes, then the row's first U splits (only splits that exist are read; all loads of
+// a batch are in flight together).  Further batches of U splits, for launches with more splits than that, update a
+// running (M, L, acc) that is rescaled when a later batch raises the maximum.
+template <typename T, int D, int WPR, int U>
 __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
     constexpr int E = D / (64 * WPR);
     static_assert(E >= 1, "at least one element per lane");
@@ -223,26 +292,28 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
     const int h = (int)(row % p.Hq);
     const long bk = row / p.Hq;
     const int k = (int)(bk % p.T_max), b = (int)(bk / p.T_max);
-    const int n = clampi(p.n_nodes[b], 0, p.T_max);
+    const int n_raw = p.n_nodes[b], P_raw = p.prefix_len[b];  // all before any is used: one trip
+    int2 share = {0, 0};
+    if (p.balanced) share = p.split_tab[b];
     T *out = static_cast<T *>(p.out);
     const size_t orow = (((size_t)b * p.T_max + k) * p.Hq + h) * D + (size_t)lane * E;
     const size_t lrow = ((size_t)b * p.Hq + h) * p.T_max + k;
-    if (k >= n) {
+    const int nvalid = p.balanced ? share.y : seq_nsplit(p, clampi(P_raw, 0, p.P_max));
+    if (k >= clampi(n_raw, 0, p.T_max)) {
 #pragma unroll
         for (int e = 0; e < E; e++) store_elem<T>(out, orow + e, 0.f);
         if (p.lse && lane == 0) p.lse[lrow] = -INFINITY;
         return;
     }
-    const int nvalid = seq_nsplit(p, seq_prefix_len(p, b));
-    const size_t pr0 = part_row(p, b, 0, h, k);
+    const size_t pr0 = part_row(p, p.balanced ? share.x : b * p.nsplit, h, k);
     const size_t sstride = (size_t)p.Hq * p.T_max;  // rows between consecutive splits
     float M = -INFINITY, L = 0.f, acc[E];
 #pragma unroll
     for (int e = 0; e < E; e++) acc[e] = 0.f;
-    for (int s0 = 0; s0 < nvalid; s0 += 8) {
-        float ms[8], ls[8], os[8][E];
+    for (int s0 = 0; s0 < nvalid; s0 += U) {
+        float ms[U], ls[U], os[U][E];
 #pragma unroll
-        for (int u = 0; u < 8; u++) {
+        for (int u = 0; u < U; u++) {
             const bool ok = s0 + u < nvalid;
             const size_t r = pr0 + (size_t)(ok ? s0 + u : 0) * sstride;
             ms[u] = ok ? p.part_m[r] : -INFINITY;
@@ -252,7 +323,7 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
         }
         float Mb = M;
 #pragma unroll
-        for (int u = 0; u < 8; u++) Mb = fmaxf(Mb, ms[u]);
+        for (int u = 0; u < U; u++) Mb = fmaxf(Mb, ms[u]);
         if (Mb == -INFINITY) continue;  // nothing visible in this batch or before
         const float keep = exp2f(M - Mb);  // 0 while M is still -inf
         L *= keep;
@@ -260,7 +331,7 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
         for (int e = 0; e < E; e++) acc[e] *= keep;
         M = Mb;
 #pragma unroll
-        for (int u = 0; u < 8; u++) {
+        for (int u = 0; u < U; u++) {
             if (ms[u] != -INFINITY) {  // absent or empty split: its l/O may be uninitialised memory
                 const float w = exp2f(ms[u] - M);
                 L = fmaf(w, ls[u], L);
@@ -685,14 +756,21 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     // with wg as the slow index the ids of one (split, KV head) differ by multiples of nsplit * Hkv, i.e. (for
     // Hkv a multiple of 8) they share an XCD and the second reader of a K/V line finds it in that XCD's L2.
     const int wg = blockIdx.y / p.Hkv, kvh = blockIdx.y % p.Hkv;
-    const int b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63;
+    SplitShare share{};
+    if (p.balanced) {  // grid (B * nsplit slots, Hkv * row groups): which sequence and split is this slot?
+        share = balanced_share(p, (int)blockIdx.x, lane);
+        if (!share.live) return;  // uniform over the workgroup
+        if (share.j == 0 && blockIdx.y == 0 && tid == 0) p.split_tab[share.b] = make_int2(share.start, share.nvalid);
+    }
+    const int b = p.balanced ? share.b : (int)blockIdx.z;
     // The split index is rotated by the sequence index.  Unrotated, split s of every sequence lands on XCD s
     // (mod 8 with the head): in a ragged batch the first splits are all full and the last ones short or absent,
     // so some XCDs carry all the long workgroups and finish half as late again as the others.  (Not rotated by
     // the KV head: in a contiguous cache the heads of a key row are neighbours in memory, and the XCD that
     // reads one of them should read all of them at about the same time.)
-    const int s = (int)((blockIdx.x + blockIdx.z) % p.nsplit);
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int s = p.balanced ? share.j : (int)((blockIdx.x + blockIdx.z) % p.nsplit);
+    const int chunk = p.balanced ? share.tps * KT : p.chunk;  // prefix keys per split of this sequence
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c32 = lane & 31, hh = lane >> 5;
 
@@ -708,12 +786,17 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     asm volatile("" ::"s"(p.q), "s"(p.k_cache), "s"(p.v_cache), "s"(p.kt), "s"(p.vt), "s"(p.block_table),
                  "s"(p.prefix_len), "s"(p.n_nodes), "s"(p.bitmask), "s"(p.T_max), "s"(p.Hq), "s"(p.G),
                  "s"(p.max_blocks), "s"(p.P_cap), "s"(p.P_max), "s"(p.words), "s"(p.chunk), "s"(p.pairs));
-    const int n_raw = ((const_i32_ptr)(uintptr_t)p.n_nodes)[b], P_raw = ((const_i32_ptr)(uintptr_t)p.prefix_len)[b];
+    int n_raw, P_raw;
+    if (p.balanced) {
+        n_raw = share.n_raw; P_raw = share.P_raw;
+    } else {
+        n_raw = ((const_i32_ptr)(uintptr_t)p.n_nodes)[b]; P_raw = ((const_i32_ptr)(uintptr_t)p.prefix_len)[b];
+    }
     // (an issuing wavefront needs ids lb, lb+1, lb+2, lb+3 of each tile: 4 * PD consecutive table entries)
     static_assert(TileLoader<NW>::U == 4 && TileLoader<NW>::NI == 4, "block ids of a tile: four consecutive entries");
     int blk_pro[PD][4];
     const int lb_first = (s * p.chunk) >> 4;
-    const bool spec = PAGED && lb_first + 4 * PD <= p.max_blocks;  // the whole range lies inside the table row
+    const bool spec = PAGED && !p.balanced && lb_first + 4 * PD <= p.max_blocks;  // the whole range lies inside the table row
     if (spec) {
         const const_i32_ptr bt_row = (const_i32_ptr)(uintptr_t)(p.block_table + (size_t)b * p.max_blocks + lb_first);
 #pragma unroll
@@ -739,7 +822,7 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
 
     const int n = clampi(n_raw, 0, p.T_max);
     const int P = clampi(P_raw, 0, p.P_max);
-    const int nvalid = seq_nsplit(p, P);
+    const int nvalid = p.balanced ? share.nvalid : seq_nsplit(p, P);
     if (s >= nvalid) return;  // uniform over the workgroup
     const bool direct = (p.nsplit == 1);
 
@@ -757,7 +840,7 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
     // wavefront-uniform: does the chunk hold any valid row?  If not the wavefront only takes part in loads and barriers
     const bool wactive = active && pair * 32 < n * p.G;
 
-    const int k0 = s * p.chunk, k1 = min(P, k0 + p.chunk);
+    const int k0 = s * chunk, k1 = min(P, k0 + chunk);
     const int nfull = (k1 > k0) ? (k1 - k0) / KT : 0;               // full prefix tiles
     const int npt = (k1 > k0) ? (k1 - k0 + KT - 1) / KT : 0;        // prefix tiles incl. a ragged last one
     const int ntt = (s == nvalid - 1) ? (n + KT - 1) / KT : 0;      // tree tiles
@@ -968,7 +1051,7 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
             }
         if (p.lse && hh == 0) p.lse[lrow] = rv ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
     } else if (rv) {
-        const size_t pr = part_row(p, b, s, h, kq);
+        const size_t pr = part_row(p, p.balanced ? (int)blockIdx.x : b * p.nsplit + s, h, kq);
 #pragma unroll
         for (int db = 0; db < 4; db++)
 #pragma unroll
@@ -990,6 +1073,7 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_mfma_kernel(AttnParams p) {
 struct Plan {
     bool mfma, kh;
     int nw, ns, pairs, wgp, chunk, nsplit;
+    bool balanced;  // split slots shared out among the sequences by their lengths, on the device
 };
 
 static bool supported(const etv_attn_desc *h) {
@@ -1061,6 +1145,8 @@ static Plan make_plan(const etv_attn_desc *h) {
             }
         }
     }
+    // a batch with splits: the slots go to the sequences by length (lane i of a wavefront plans sequence i)
+    pl.balanced = pl.nsplit > 1 && B >= 2 && B <= 64 && !(h->flags & ETV_ATTN_FLAG_UNIFORM_SPLITS);
     if (best == 1e30) {  // kv_split larger than the prefix: a single split
         pl.nw = (pl.pairs > 4 && !(h->flags & ETV_ATTN_FLAG_SMALL_WG)) ? 8 : 4;
         pl.kh = false;
@@ -1094,6 +1180,7 @@ extern "C" int32_t etv_tree_verify_attention_plan(const etv_attn_desc *h, etv_at
     out->row_groups = pl.mfma ? pl.wgp : 0;
     out->kv_split = pl.chunk;
     out->n_splits = pl.nsplit;
+    out->balanced_splits = pl.mfma && pl.balanced ? 1 : 0;
     out->workgroups = pl.mfma ? (int64_t)pl.nsplit * h->Hkv * pl.wgp * (h->B > 0 ? h->B : 0)
                               : (int64_t)h->T_max * h->Hq * (h->B > 0 ? h->B : 0) * pl.nsplit;
     return ETV_OK;
@@ -1104,7 +1191,7 @@ extern "C" size_t etv_tree_verify_attention_workspace_bytes(const etv_attn_desc 
     etv::Plan pl = etv::make_plan(h);
     if (pl.nsplit <= 1) return 256;
     size_t rows = (size_t)h->B * h->Hq * h->T_max * pl.nsplit;
-    return rows * ((size_t)h->d + 2) * sizeof(float) + 512;
+    return rows * ((size_t)h->d + 2) * sizeof(float) + 1024;  // partials, then 64 (first slot, splits) pairs
 }
 
 namespace etv {
@@ -1156,11 +1243,13 @@ static int32_t attention_run(const etv_attn_desc *h, const void *q, const void *
         p.part_o = static_cast<float *>(workspace);
         p.part_m = p.part_o + rows * h->d;
         p.part_l = p.part_m + rows;
+        p.split_tab = reinterpret_cast<int2 *>(p.part_l + rows);  // 8-byte aligned: rows * (d + 2) floats in
+        p.balanced = pl.mfma && pl.balanced;
     }
     hipStream_t st = as_stream(stream);
     int32_t rc;
     if (pl.mfma) {
-        dim3 grid(pl.nsplit, h->Hkv * pl.wgp, h->B);
+        const dim3 grid = pl.balanced ? dim3(pl.nsplit * h->B, h->Hkv * pl.wgp, 1) : dim3(pl.nsplit, h->Hkv * pl.wgp, h->B);
         const bool paged = h->block_size > 0;
         // 8 wavefronts: one workgroup per compute unit with a 4-stage ring (128 KiB of LDS);
         // 4 wavefronts: two workgroups per compute unit with 2 stages each, or 4 stages when the grid is small
@@ -1194,19 +1283,20 @@ static int32_t attention_run(const etv_attn_desc *h, const void *q, const void *
     if (rc != ETV_OK || pl.nsplit == 1) return rc;
     const long crows = (long)h->B * h->T_max * h->Hq;
     const bool two = h->d == 128 && crows <= 512;  // very few rows: two wavefronts per row
+    const bool wide = pl.nsplit > 8;                // many splits: sixteen per batch of loads
     dim3 cgrid((unsigned)((crows + (two ? 1 : 3)) / (two ? 2 : 4)));
-    if (h->dtype == ETV_F32 && h->d == 64)
-        hipLaunchKernelGGL((attn_combine_kernel<float, 64, 1>), cgrid, dim3(256), 0, st, p);
-    else if (h->dtype == ETV_F32 && two)
-        hipLaunchKernelGGL((attn_combine_kernel<float, 128, 2>), cgrid, dim3(256), 0, st, p);
-    else if (h->dtype == ETV_F32)
-        hipLaunchKernelGGL((attn_combine_kernel<float, 128, 1>), cgrid, dim3(256), 0, st, p);
-    else if (h->d == 64)
-        hipLaunchKernelGGL((attn_combine_kernel<uint16_t, 64, 1>), cgrid, dim3(256), 0, st, p);
-    else if (two)
-        hipLaunchKernelGGL((attn_combine_kernel<uint16_t, 128, 2>), cgrid, dim3(256), 0, st, p);
-    else
-        hipLaunchKernelGGL((attn_combine_kernel<uint16_t, 128, 1>), cgrid, dim3(256), 0, st, p);
+#define ETV_COMBINE(TY, DD, WPR) \
+    do { \
+        if (wide) hipLaunchKernelGGL((attn_combine_kernel<TY, DD, WPR, 16>), cgrid, dim3(256), 0, st, p); \
+        else hipLaunchKernelGGL((attn_combine_kernel<TY, DD, WPR, 8>), cgrid, dim3(256), 0, st, p); \
+    } while (0)
+    if (h->dtype == ETV_F32 && h->d == 64) ETV_COMBINE(float, 64, 1);
+    else if (h->dtype == ETV_F32 && two) ETV_COMBINE(float, 128, 2);
+    else if (h->dtype == ETV_F32) ETV_COMBINE(float, 128, 1);
+    else if (h->d == 64) ETV_COMBINE(uint16_t, 64, 1);
+    else if (two) ETV_COMBINE(uint16_t, 128, 2);
+    else ETV_COMBINE(uint16_t, 128, 1);
+#undef ETV_COMBINE
     return check_launch();
 }
 }  // namespace etv

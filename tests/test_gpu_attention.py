@@ -183,6 +183,35 @@ def test_long_prefix_and_many_sequences():
     _check(wl)
 
 
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("B,T,kv_split", [(2, 40, 64), (7, 60, 256), (8, 200, 128), (64, 12, 64), (65, 12, 64)])
+def test_splits_shared_out_by_length_agree_with_the_oracle(paged, B, T, kv_split):
+    """Ragged batches with splits: up to 64 sequences the launch's split slots follow the sequences' lengths (every
+    sequence cuts its own prefix evenly over its share); the uniform split size is kept beyond 64 sequences and on
+    request.  Both against the oracle, with empty prefixes, empty trees and prefixes of a few keys in the batch."""
+    rng = np.random.default_rng(4200 + B + T)
+    hi = 2000 if B <= 8 else 300
+    P = [int(x) for x in rng.integers(0, hi + 1, size=B)]
+    n = [int(x) for x in rng.integers(1, T + 1, size=B)]
+    P[0], n[0] = hi, T           # the longest sequence sizes the launch
+    P[1] = 0                     # no prefix at all
+    if B > 2:
+        P[2], n[2] = 0, 0        # nothing at all
+        P[3], n[3] = 65, 0       # a prefix but no tree
+        P[-1] = 3
+    wl = _small(rng, B, T, 8, 2, 128, P, "bf16", paged, n_nodes=n, q_scale=2.0)
+    d = DevWorkload(wl)
+
+    def desc(flags):
+        return api.attn_desc(d.q, d.kt, d.k_cache, d.block_table, d.P_max, kv_split=kv_split, flags=flags)
+    plan = api.tree_verify_attention_plan(desc(0))
+    assert plan["n_splits"] > 1 and plan["balanced_splits"] == (1 if B <= 64 else 0)
+    uniform = api.tree_verify_attention_plan(desc(api.ATTN_FLAG_UNIFORM_SPLITS))
+    assert uniform["balanced_splits"] == 0 and uniform["n_splits"] == plan["n_splits"]
+    _check(wl, kv_split=kv_split)
+    _check(wl, kv_split=kv_split, flags=api.ATTN_FLAG_UNIFORM_SPLITS)
+
+
 def test_no_leak_from_hidden_tree_rows_padding_and_stale_cache_bf16():
     rng = np.random.default_rng(800)
     wl = _small(rng, 1, 48, 8, 2, 128, [100], "bf16", False, n_nodes=[37])
