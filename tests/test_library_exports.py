@@ -70,6 +70,16 @@ def test_launch_plan_is_reported_and_follows_the_tuning_flags():
     assert forced["kv_split"] == 512 and forced["n_splits"] == 4 and forced["key_halves"] == 0 and forced["wavefronts"] == 4
     large = api.tree_verify_attention_plan(desc(1, 60, 2048, False, flags=api.ATTN_FLAG_LARGE_WG | api.ATTN_FLAG_WHOLE_TILE))
     assert large["wavefronts"] == 8 and large["key_halves"] == 0
+    # split slots follow the sequences' lengths for batches of 2 .. 64 sequences, unless the flag keeps one split size
+    assert big["balanced_splits"] == 0 and c2["balanced_splits"] == 0             # no splits / one sequence
+    ragged = api.tree_verify_attention_plan(desc(8, 60, 8192, True))
+    assert ragged["n_splits"] > 1 and ragged["balanced_splits"] == 1
+    assert ragged["workgroups"] == 8 * ragged["n_splits"] * 8 * ragged["row_groups"]
+    kept = api.tree_verify_attention_plan(desc(8, 60, 8192, True, flags=api.ATTN_FLAG_UNIFORM_SPLITS))
+    assert kept["balanced_splits"] == 0 and kept["n_splits"] == ragged["n_splits"]
+    assert api.tree_verify_attention_plan(desc(65, 12, 8192, True, kv_split=1024))["balanced_splits"] == 0
+    ws = api.tree_verify_attention_workspace_bytes(desc(8, 60, 8192, True))
+    assert ws >= 8 * ragged["n_splits"] * 32 * 60 * 130 * 4 + 64 * 8                  # partials + the split table
     f32 = api.AttnDesc(B=1, T_max=15, Hq=4, Hkv=4, d=64, dtype=api.F32, block_size=0, max_blocks=0, num_blocks=0,
                        P_cap=200, P_max=128, scale=0.0, kv_split=0, flags=0)
     assert api.tree_verify_attention_plan(f32)["mfma"] == 0
