@@ -37,6 +37,16 @@ ETVP_API int32_t etvp_hbm_read_probe(const void *buf, size_t bytes, void *sink, 
 ETVP_API double etvp_mfma_bf16_probe_flops(int32_t iters);
 ETVP_API int32_t etvp_mfma_bf16_probe(int32_t iters, void *sink, void *stream);
 
+/* The matrix instructions of an attention launch and nothing else (no memory traffic, no barrier, no softmax): 512
+ * workgroups of 8 wavefronts, one per compute unit, each wavefront issuing per "tile" the 16 score products (two
+ * fresh chains) and 16 value products (four running chains) that the attention kernel issues for 32 query rows and
+ * 64 keys, on operands that change from product to product and from tile to tile.  The clock of the chip falls
+ * with the switching activity in the matrix cores, so this rate is lower than the loop above reaches on operands
+ * that never change; it is what the matrix part of the attention launch costs on this machine.  `tiles`: 1 ..
+ * 2^20 (66 is the headline sweep cell: 283 GFLOP per launch); sink as above. */
+ETVP_API double etvp_mfma_bf16_live_probe_flops(int32_t tiles);
+ETVP_API int32_t etvp_mfma_bf16_live_probe(int32_t tiles, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

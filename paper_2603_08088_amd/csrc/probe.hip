@@ -71,6 +71,72 @@ __global__ void __launch_bounds__(256, 2) mfma_bf16_probe_kernel(int iters, floa
     if (iters < 0) sink[0] = s;  // never true: keeps the products alive
 }
 
+// The matrix instructions of an attention launch and nothing else: 512 workgroups of 8 wavefronts, one workgroup per
+// compute unit (two wavefronts per SIMD, two rounds on 256 compute units); per 64-key "tile" a wavefront issues 16 score
+// products (two fresh chains of eight) and 16 value products (four running chains), as the attention kernel does for
+// 32 query rows.  Unlike the loop above the operands change from product to product and from tile to tile: the "K"
+// and "V" fragments are re-randomised every tile (sign and mantissa bits), the "P" operands are made from the bits of
+// the scores just computed.  No memory traffic, no barrier, nothing to wait for.
+constexpr int kLiveGrid = 512;
+__global__ void __launch_bounds__(512, 2) mfma_bf16_live_probe_kernel(int tiles, float *sink) {
+    extern __shared__ uint32_t occupy[];     // 96 KiB of dynamic LDS: keeps a second workgroup off the compute unit
+    const uint32_t id = blockIdx.x * 512u + threadIdx.x;
+    if (tiles < 0) occupy[threadIdx.x] = id;  // never true
+    u32x4 kf[8], vf[8], q[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            kf[i][j] = (mix(id * 128u + i * 4u + j) & 0x80ff80ffu) | 0x3f003f00u;
+            vf[i][j] = (mix(id * 128u + 32u + i * 4u + j) & 0x80ff80ffu) | 0x3f003f00u;
+            q[i][j] = (mix(id * 128u + 64u + i * 4u + j) & 0x80ff80ffu) | 0x3f003f00u;
+        }
+    f32x16 o[4];
+#pragma unroll
+    for (int c = 0; c < 4; c++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) o[c][i] = 0.f;
+    uint32_t salt = mix(id);
+    for (int t = 0; t < tiles; t++) {
+        f32x16 s0, s1;
+#pragma unroll
+        for (int i = 0; i < 16; i++) { s0[i] = 0.f; s1[i] = 0.f; }
+#pragma unroll
+        for (int kk = 0; kk < 8; kk++) {
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[kk]), __builtin_bit_cast(bf16x8, q[kk]), s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[kk]), __builtin_bit_cast(bf16x8, q[kk]), s1, 0, 0, 0);
+        }
+        // "probabilities": bf16 pairs in [0.5, 2) with the sign and mantissa bits of the scores
+        u32x4 pf[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const float x = (i & 1) ? s1[4 * (i >> 1) + j] : s0[4 * (i >> 1) + j];
+                pf[i][j] = (__float_as_uint(x) & 0x807f807fu) | 0x3f003f00u;
+            }
+#pragma unroll
+        for (int st = 0; st < 4; st++)
+#pragma unroll
+            for (int c = 0; c < 4; c++)
+                o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, (st & 1) ? vf[(st + c) & 7] : kf[(st + c) & 7]),
+                                                               __builtin_bit_cast(bf16x8, pf[st]), o[c], 0, 0, 0);
+        // the next tile's fragments: new sign and mantissa bits
+        salt = salt * 1664525u + 1013904223u;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            kf[i][i & 3] ^= (salt >> i) & 0x807f807fu;
+            vf[i][(i + 1) & 3] ^= (salt << i) & 0x807f807fu;
+        }
+    }
+    float acc = 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; c++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) acc += o[c][i];
+    if (tiles < 0) sink[0] = acc + (float)occupy[0];  // never true: keeps the products alive
+}
+
 }  // namespace etvp
 
 extern "C" int32_t etvp_hbm_read_probe(const void *buf, size_t bytes, void *sink, void *stream) {
@@ -88,5 +154,20 @@ extern "C" int32_t etvp_mfma_bf16_probe(int32_t iters, void *sink, void *stream)
     if (!sink || iters < 1 || iters > (1 << 20)) return -1;
     hipLaunchKernelGGL(etvp::mfma_bf16_probe_kernel, dim3(etvp::kMfmaGrid), dim3(256), 0,
                        reinterpret_cast<hipStream_t>(stream), iters, static_cast<float *>(sink));
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+extern "C" double etvp_mfma_bf16_live_probe_flops(int32_t tiles) {
+    return (double)etvp::kLiveGrid * 8.0 * (double)tiles * 32.0 * (2.0 * 32 * 32 * 16);
+}
+
+extern "C" int32_t etvp_mfma_bf16_live_probe(int32_t tiles, void *sink, void *stream) {
+    if (!sink || tiles < 1 || tiles > (1 << 20)) return -1;
+    constexpr int lds = 96 * 1024;
+    static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&etvp::mfma_bf16_live_probe_kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess;
+    if (!lds_ok) return -4;
+    hipLaunchKernelGGL(etvp::mfma_bf16_live_probe_kernel, dim3(etvp::kLiveGrid), dim3(512), lds,
+                       reinterpret_cast<hipStream_t>(stream), tiles, static_cast<float *>(sink));
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }

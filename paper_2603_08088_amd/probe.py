@@ -8,7 +8,8 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libeagletv_probe.so")
-EXPORTS = ("etvp_hbm_read_probe", "etvp_mfma_bf16_probe_flops", "etvp_mfma_bf16_probe")
+EXPORTS = ("etvp_hbm_read_probe", "etvp_mfma_bf16_probe_flops", "etvp_mfma_bf16_probe",
+           "etvp_mfma_bf16_live_probe_flops", "etvp_mfma_bf16_live_probe")
 _lib = None
 
 
@@ -24,6 +25,10 @@ def lib():
         l.etvp_mfma_bf16_probe_flops.argtypes = [C.c_int32]
         l.etvp_mfma_bf16_probe.restype = C.c_int32
         l.etvp_mfma_bf16_probe.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
+        l.etvp_mfma_bf16_live_probe_flops.restype = C.c_double
+        l.etvp_mfma_bf16_live_probe_flops.argtypes = [C.c_int32]
+        l.etvp_mfma_bf16_live_probe.restype = C.c_int32
+        l.etvp_mfma_bf16_live_probe.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
         _lib = l
     return _lib
 
@@ -47,3 +52,13 @@ def mfma_bf16_probe(iters: int, sink: torch.Tensor) -> None:
     rc = lib().etvp_mfma_bf16_probe(int(iters), sink.data_ptr(), _stream())
     if rc != 0:
         raise RuntimeError(f"etvp_mfma_bf16_probe: rc={rc}")
+
+
+def mfma_bf16_live_probe_flops(tiles: int) -> float:
+    return float(lib().etvp_mfma_bf16_live_probe_flops(int(tiles)))
+
+
+def mfma_bf16_live_probe(tiles: int, sink: torch.Tensor) -> None:
+    rc = lib().etvp_mfma_bf16_live_probe(int(tiles), sink.data_ptr(), _stream())
+    if rc != 0:
+        raise RuntimeError(f"etvp_mfma_bf16_live_probe: rc={rc}")
