@@ -270,14 +270,18 @@ def test_probe_library_runs_and_rejects_bad_arguments():
     sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
     probe.hbm_read_probe(buf, sink)
     probe.mfma_bf16_probe(4, sink)
+    probe.mfma_bf16_live_probe(3, sink)
     torch.cuda.synchronize()
     assert int(sink.sum().item()) == 0
+    assert probe.mfma_bf16_live_probe_flops(66) == 512 * 8 * 66 * 32 * 2.0 * 32 * 32 * 16
     with pytest.raises(RuntimeError):
         probe.hbm_read_probe(buf[: 2 ** 16], sink)   # below the 1 MiB minimum
     with pytest.raises(RuntimeError):
         probe.hbm_read_probe(buf[1:], sink)          # misaligned
     with pytest.raises(RuntimeError):
         probe.mfma_bf16_probe(0, sink)
+    with pytest.raises(RuntimeError):
+        probe.mfma_bf16_live_probe(0, sink)
 
 
 def _epilogue_case(wl, L=2, dummy=0, spoil=None):

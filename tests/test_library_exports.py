@@ -27,7 +27,7 @@ def test_header_symbols_are_exported_and_binding_lists_them_all():
 def test_probe_library_exports_its_header_and_the_product_library_holds_no_probe():
     from paper_2603_08088_amd import probe
     syms = _declared_symbols("eagletv_probe.h", "etvp_")
-    assert sorted(probe.EXPORTS) == syms and len(syms) == 3
+    assert sorted(probe.EXPORTS) == syms and len(syms) == 5
     lib = ctypes.CDLL(probe.LIB_PATH)
     for s in syms:
         assert hasattr(lib, s), s
